@@ -1,0 +1,470 @@
+"""Pins of the CPU oracle: every function is checked against something other than itself --
+values the paper states (tests/golden/paper_constants.txt), closed forms, invariants, brute
+force on tiny inputs.  No GPU needed."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_15689_amd import synth_inputs as si
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_constants.txt")
+
+
+def paper_constants():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, val = line.split()
+            out[name] = float(val)
+    return out
+
+
+def popcount(x: int) -> int:
+    return bin(x).count("1")
+
+
+# ---------------------------------------------------------------- Hadamard matrices
+
+@pytest.mark.parametrize("n", [1, 2, 4, 8, 16, 64, 256])
+def test_sylvester_orthogonal_and_closed_form(n):
+    H = oracle.hadamard_sylvester(n).astype(np.int64)
+    assert set(np.unique(H)) <= {-1, 1}
+    assert (H @ H.T == n * np.eye(n, dtype=np.int64)).all()        # H H^T = n I  (Sec. 3.1)
+    assert (H == H.T).all()
+    closed = np.array([[(-1) ** popcount(i & j) for j in range(n)] for i in range(n)])
+    assert (H == closed).all()
+
+
+def test_gf27_is_a_field_with_the_stated_modulus():
+    from oracle import basq_oracle as bo
+    add = lambda x, y: bo._gf27_sub(x, bo._gf27_sub(0, y))
+    mul = bo._gf27_mul
+    t = 3                                      # the element "t"
+    t3 = mul(t, mul(t, t))
+    assert add(add(t3, mul(2, t)), 1) == 0     # t^3 + 2t + 1 = 0
+    for x in range(1, 27):                     # every non-zero element has an inverse
+        assert sum(1 for y in range(1, 27) if mul(x, y) == 1) == 1
+        assert mul(x, 1) == x and mul(x, 0) == 0
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        a, b, c = (int(v) for v in rng.integers(0, 27, 3))
+        assert mul(a, b) == mul(b, a)
+        assert mul(a, mul(b, c)) == mul(mul(a, b), c)
+        assert mul(a, add(b, c)) == add(mul(a, b), mul(a, c))
+    sq = oracle.gf27_squares()
+    assert len(sq) == 13
+    assert bo._gf27_sub(0, 1) not in sq        # -1 is a non-square since 27 = 3 mod 4 -> Q is skew
+
+
+def test_paley28_is_hadamard_and_skew():
+    H = oracle.hadamard_paley28().astype(np.int64)
+    assert H.shape == (28, 28)
+    assert set(np.unique(H)) == {-1, 1}
+    assert (H @ H.T == 28 * np.eye(28, dtype=np.int64)).all()
+    assert (H.T @ H == 28 * np.eye(28, dtype=np.int64)).all()
+    S = H - np.eye(28, dtype=np.int64)
+    assert (S == -S.T).all()                   # Paley type I: H = I + S with S skew-symmetric
+    assert (H[0, :] == 1).all() and (H[1:, 0] == -1).all()
+    assert not (H == H.T).all()
+
+
+@pytest.mark.parametrize("n", [28, 56, 448])
+def test_kronecker_matrix_orthogonal_and_indexing(n):
+    H = oracle.hadamard_matrix(n).astype(np.int64)
+    assert (H @ H.T == n * np.eye(n, dtype=np.int64)).all()
+    H28 = oracle.hadamard_paley28().astype(np.int64)
+    Hs = oracle.hadamard_sylvester(n // 28).astype(np.int64)
+    m = n // 28
+    rng = np.random.default_rng(1)
+    for _ in range(200):                       # entry [(i,j),(i',j')] = H28[i,i'] * Hs[j,j'], k = i*m + j
+        i, ii = rng.integers(0, 28, 2)
+        j, jj = rng.integers(0, m, 2)
+        assert H[i * m + j, ii * m + jj] == H28[i, ii] * Hs[j, jj]
+
+
+def test_kronecker_14336_sampled_rows_orthogonal():
+    H = oracle.hadamard_matrix(14336)
+    assert H.shape == (14336, 14336) and H.dtype == np.int8
+    rng = np.random.default_rng(2)
+    rows = rng.choice(14336, size=24, replace=False)
+    sub = H[rows].astype(np.int64)
+    assert (sub @ sub.T == 14336 * np.eye(24, dtype=np.int64)).all()
+    assert (np.abs(sub) == 1).all()
+
+
+# ---------------------------------------------------------------- rotation
+
+def brute_rotate(x, H):
+    M, n = x.shape
+    out = np.zeros((M, n))
+    for m in range(M):
+        for j in range(n):
+            acc = Fraction(0)
+            for k in range(n):
+                acc += Fraction(float(x[m, k])) * int(H[k, j])
+            out[m, j] = float(acc) / math.sqrt(n)
+    return out
+
+
+@pytest.mark.parametrize("n", [2, 8, 28, 56])
+def test_rotate_matches_brute_force(n):
+    rng = np.random.default_rng(n)
+    x = rng.standard_normal((3, n)).astype(np.float32)
+    H = oracle.hadamard_matrix(n)
+    r = oracle.rotate(x, n)
+    ref = brute_rotate(x, H)
+    assert r.dtype == np.float32
+    np.testing.assert_allclose(r, ref.astype(np.float32), rtol=0, atol=1e-6)
+
+
+def test_rotate_blocks_are_independent():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((4, 64)).astype(np.float32)
+    r = oracle.rotate(x, 16)
+    for b in range(4):
+        np.testing.assert_array_equal(r[:, 16 * b:16 * b + 16], oracle.rotate(x[:, 16 * b:16 * b + 16], 16))
+
+
+@pytest.mark.parametrize("n", [64, 1024, 56, 448])
+def test_rotation_preserves_energy_and_inverts(n):
+    rng = np.random.default_rng(10 + n)
+    x = rng.standard_normal((5, n))
+    r = oracle.rotate_f64(x, n)
+    np.testing.assert_allclose((r ** 2).sum(1), (x ** 2).sum(1), rtol=1e-12)      # orthogonal: energy preserved
+    Rt = oracle.hadamard_matrix(n).astype(np.float64).T / math.sqrt(n)
+    np.testing.assert_allclose(r @ Rt, x, atol=1e-12)                              # x R R^T = x
+
+
+@pytest.mark.parametrize("n", [64, 4096, 56])
+def test_outlier_is_spread_evenly(n):
+    c = paper_constants()
+    a = 37.0
+    for chan in (0, 1, n - 1):
+        x = np.zeros((1, n))
+        x[0, chan] = a
+        r = oracle.rotate_f64(x, n)[0]
+        np.testing.assert_allclose(np.abs(r), a * n ** c["outlier_spread_exponent"], rtol=1e-12)
+        # x = e_chan picks ROW chan of H (x . H): for the non-symmetric H_28 this fixes the side
+        np.testing.assert_array_equal(np.sign(r), oracle.hadamard_matrix(n)[chan].astype(np.float64))
+    if n == 56:
+        assert (oracle.rotate_f64(np.eye(1, n), n) > 0).all()       # row 0 of H_28 (x) H_2 is all +1
+
+
+def test_kronecker_rotation_is_the_two_factor_sum():
+    rng = np.random.default_rng(7)
+    n, m = 56, 2
+    x = rng.standard_normal((2, n))
+    H28 = oracle.hadamard_paley28().astype(np.float64)
+    Hs = oracle.hadamard_sylvester(m).astype(np.float64)
+    ref = np.zeros_like(x)
+    for t in range(2):
+        for ii in range(28):
+            for jj in range(m):
+                s = 0.0
+                for i in range(28):
+                    for j in range(m):
+                        s += x[t, i * m + j] * H28[i, ii] * Hs[j, jj]
+                ref[t, ii * m + jj] = s / math.sqrt(n)
+    np.testing.assert_allclose(oracle.rotate_f64(x, n), ref, atol=1e-12)
+
+
+# ---------------------------------------------------------------- storage formats
+
+def exact_bf16_rne(y: float) -> int:
+    """bf16 bits of y by exact rational arithmetic (finite, normal range)."""
+    if y == 0:
+        return 0x8000 if math.copysign(1, y) < 0 else 0
+    sign = 0x8000 if y < 0 else 0
+    fy = Fraction(abs(y))
+    e = math.floor(math.log2(abs(y)))
+    while Fraction(2) ** e > fy:
+        e -= 1
+    while Fraction(2) ** (e + 1) <= fy:
+        e += 1
+    q = fy / Fraction(2) ** (e - 7)            # in [128, 256)
+    fl = math.floor(q)
+    rem = q - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        fl += 1
+    if fl == 256:
+        fl, e = 128, e + 1
+    return sign | ((e + 127) << 7) | (fl - 128)
+
+
+def test_f64_to_bf16_single_rounding():
+    rng = np.random.default_rng(3)
+    vals = list(rng.standard_normal(2000) * 10.0 ** rng.integers(-3, 4, 2000))
+    # adversarial: just above / below a bf16 tie by less than half an fp32 ulp
+    for base in (1.0, 1.0078125, 3.5, 100.0, -2.0):
+        b = np.float32(base).view(np.uint32) & np.uint32(0xFFFF0000)
+        tie = float((b | np.uint32(0x8000)).view(np.float32))
+        for eps in (1e-12, -1e-12, 3e-9, -3e-9, 0.0):
+            vals.append(tie * (1 + eps))
+    vals = np.array(vals, dtype=np.float64)
+    got = oracle.f64_to_bf16(vals)
+    exp = np.array([exact_bf16_rne(float(v)) for v in vals], dtype=np.uint16)
+    np.testing.assert_array_equal(got, exp)
+    # round trip of exact bf16 values
+    bits = rng.integers(0x0080, 0x7F7F, 1000).astype(np.uint16)
+    np.testing.assert_array_equal(oracle.f64_to_bf16(oracle.bf16_to_f32(bits)), bits)
+
+
+def test_pack_unpack_nibble_order():
+    q = np.arange(16, dtype=np.uint8).reshape(1, 16)
+    p = oracle.pack_codes(q)
+    assert p[0, 0] == 0x10 and p[0, 7] == 0xFE          # low nibble = even k
+    np.testing.assert_array_equal(oracle.unpack_codes(p), q)
+
+
+# ---------------------------------------------------------------- activation quantiser (Eq. 4)
+
+def test_range_ends_map_to_0_and_15_without_clipping():
+    rng = np.random.default_rng(11)
+    v = rng.standard_normal((64, 512)).astype(np.float32) * 3 + 1
+    tq = oracle.quantize_tokens(v, None, None, 1.0, 1.0)
+    for m in range(64):
+        assert tq.codes[m, v[m].argmin()] == 0
+        assert tq.codes[m, v[m].argmax()] == 15
+        assert tq.lo[m, 0] == v[m].min()
+        np.testing.assert_allclose(tq.scale[m, 0], (v[m].max() - v[m].min()) / 15, rtol=1e-6)
+    assert tq.codes.max() == 15 and tq.codes.min() == 0
+    np.testing.assert_array_equal(tq.rowsum[:, 0], tq.codes.astype(np.int64).sum(1))
+
+
+def test_codes_follow_eq4_in_exact_arithmetic():
+    """q = clip(round((v - z)/s), 0, 15) evaluated in fp64 from the oracle's own z and s: the fp32
+    sequence may differ only where (v - z)/s sits on a rounding boundary."""
+    rng = np.random.default_rng(12)
+    r = rng.standard_normal((128, 1024)).astype(np.float32)
+    bias = (rng.standard_normal(1024) * 0.3).astype(np.float32)
+    tq = oracle.quantize_tokens(r, bias, None, 0.9, 0.8)
+    v = r.astype(np.float64) - bias.astype(np.float64)
+    # range: lo = clip_lo * min, hi = clip_hi * max  (this build's reading of the clip ratio)
+    np.testing.assert_allclose(tq.lo[:, 0], 0.9 * v.min(1), rtol=1e-6)
+    np.testing.assert_allclose(tq.scale[:, 0], (0.8 * v.max(1) - 0.9 * v.min(1)) / 15, rtol=1e-6)
+    t = (v - tq.lo.astype(np.float64)) / tq.scale.astype(np.float64)
+    ref = np.clip(np.rint(t), 0, 15)
+    diff = tq.codes.astype(np.int64) - ref.astype(np.int64)
+    bad = diff != 0
+    assert bad.mean() < 1e-4
+    assert (np.abs(diff[bad]) == 1).all()
+    frac = np.abs(t[bad] - np.floor(t[bad]) - 0.5)
+    assert (frac < 1e-4).all()
+    assert (tq.codes == 0).any() and (tq.codes == 15).any()      # both clip ends are exercised
+
+
+def test_roundtrip_error_at_most_half_a_step_when_unclipped():
+    rng = np.random.default_rng(13)
+    v = rng.standard_normal((32, 2048)).astype(np.float32)
+    tq = oracle.quantize_tokens(v, None, None, 1.0, 1.0)
+    xhat = oracle.dequantize_tokens(tq)
+    err = np.abs(xhat - v.astype(np.float64))
+    assert (err <= tq.scale.astype(np.float64) / 2 * (1 + 1e-5)).all()
+
+
+def test_rounding_energy_is_s2_over_12():
+    c = paper_constants()
+    rng = np.random.default_rng(14)
+    v = rng.uniform(-1, 1, size=(8, 1 << 17)).astype(np.float32)
+    tq = oracle.quantize_tokens(v, None, None, 1.0, 1.0)
+    err = oracle.dequantize_tokens(tq) - v.astype(np.float64)
+    ratio = (err ** 2).mean(1) / tq.scale[:, 0].astype(np.float64) ** 2
+    np.testing.assert_allclose(ratio, c["rounding_energy_coeff"], rtol=0.02)
+
+
+def test_clipped_energy_of_a_gaussian_at_2p2_sigma():
+    """Fix the range at +-2.2 sigma with two sentinels (+-4.4, clip ratio 0.5): the energy of the
+    elements the quantiser saturates is the 18.4 % the paper states."""
+    c = paper_constants()
+    rng = np.random.default_rng(15)
+    K = 1 << 20
+    v = rng.standard_normal((1, K)).astype(np.float32)
+    v = np.clip(v, -4.3, 4.3)
+    v[0, 0], v[0, 1] = -2 * c["clip_sigma"], 2 * c["clip_sigma"]
+    tq = oracle.quantize_tokens(v, None, None, 0.5, 0.5)
+    assert abs(tq.lo[0, 0] + c["clip_sigma"]) < 1e-6
+    assert abs(tq.scale[0, 0] * 15 - 2 * c["clip_sigma"]) < 1e-5
+    xhat = oracle.dequantize_tokens(tq)
+    body = slice(2, None)
+    vv = v[0, body].astype(np.float64)
+    lo, hi = float(tq.lo[0, 0]), float(tq.lo[0, 0]) + 15 * float(tq.scale[0, 0])
+    below, above = vv < lo, vv > hi
+    saturated = below | above                                     # the mass outside [z, z + Delta]
+    assert (tq.codes[0, body][below] == 0).all() and (tq.codes[0, body][above] == 15).all()
+    inside_err = np.abs(xhat[0, body] - vv)[~saturated]
+    assert (inside_err <= tq.scale[0, 0] / 2 * (1 + 1e-5)).all()
+    loss = (vv[saturated] ** 2).sum() / (vv ** 2).sum()
+    closed = 2 * (2.2 * math.exp(-2.2 ** 2 / 2) / math.sqrt(2 * math.pi) + 0.5 * math.erfc(2.2 / math.sqrt(2)))
+    assert abs(closed - c["clip_energy_loss"]) < 5e-4             # the paper's figure is the closed form
+    assert abs(loss - closed) < 4e-3                              # Monte-Carlo error at 1M samples
+
+
+def test_asymmetric_scale_and_bias_order():
+    """Eq. 15: the scale multiplies the rotated activation BEFORE the bias is subtracted."""
+    rng = np.random.default_rng(16)
+    r = rng.standard_normal((16, 256)).astype(np.float32)
+    sa = rng.uniform(0.5, 2.0, 256).astype(np.float32)
+    b = rng.standard_normal(256).astype(np.float32)
+    tq = oracle.quantize_tokens(r, b, sa, 1.0, 1.0)
+    v = r.astype(np.float64) * sa - b
+    np.testing.assert_allclose(tq.lo[:, 0], v.min(1), rtol=1e-6)
+    np.testing.assert_allclose(oracle.dequantize_tokens(tq), v, atol=float(tq.scale.max()) / 2 * 1.001)
+    wrong = (r.astype(np.float64) - b) * sa
+    assert not np.allclose(tq.lo[:, 0], wrong.min(1), rtol=1e-3)
+
+
+def test_groupwise_equals_per_token_on_reshaped_input():
+    rng = np.random.default_rng(17)
+    r = rng.standard_normal((8, 512)).astype(np.float32)
+    tg = oracle.quantize_tokens(r, None, None, 0.9, 0.9, group_size=128)
+    tt = oracle.quantize_tokens(r.reshape(32, 128), None, None, 0.9, 0.9)
+    np.testing.assert_array_equal(tg.codes.reshape(32, 128), tt.codes)
+    np.testing.assert_array_equal(tg.scale.reshape(-1), tt.scale.reshape(-1))
+    np.testing.assert_array_equal(tg.rowsum.reshape(-1), tt.rowsum.reshape(-1))
+
+
+def test_degenerate_tokens():
+    v = np.full((1, 64), 3.25, dtype=np.float32)
+    tq = oracle.quantize_tokens(v, None, None, 1.0, 1.0)
+    assert tq.scale[0, 0] == 1.0 and (tq.codes == 0).all() and tq.lo[0, 0] == 3.25
+    np.testing.assert_array_equal(oracle.dequantize_tokens(tq), v.astype(np.float64))
+    v = np.linspace(-1, 1, 64, dtype=np.float32).reshape(1, 64)
+    ref = oracle.quantize_tokens(v, None, None, 1.0, 1.0)
+    v2 = v.copy()
+    v2[0, 5] = np.nan
+    tq = oracle.quantize_tokens(v2, None, None, 1.0, 1.0)
+    assert tq.codes[0, 5] == 0                                    # NaN -> code 0, range ignores it
+    assert tq.scale[0, 0] == ref.scale[0, 0] and tq.lo[0, 0] == ref.lo[0, 0]
+    keep = np.arange(64) != 5
+    np.testing.assert_array_equal(tq.codes[0, keep], ref.codes[0, keep])
+
+
+# ---------------------------------------------------------------- weight quantiser
+
+def test_weight_quantiser_properties():
+    rng = np.random.default_rng(20)
+    w = (rng.standard_normal((64, 512)) * 0.02).astype(np.float32)
+    w = oracle.bf16_to_f32(oracle.f64_to_bf16(w))
+    w[3, :] = np.abs(w[3, :])                  # an all-positive row: zero-point clamps at 0
+    w[5, 10] = 0.0
+    wq = oracle.quantize_weights(w)
+    sw, zp = wq.scale.astype(np.float64), wq.zero.astype(np.float64)
+    assert (zp == np.rint(zp)).all() and (zp >= 0).all() and (zp <= 15).all()
+    assert zp[3] == 0
+    np.testing.assert_allclose(sw, (w.max(1) - w.min(1)).astype(np.float64) / 15, rtol=2 ** -8)
+    what = oracle.dequantize_weights(wq)
+    assert what[5, 10] == 0.0                  # zero is represented exactly (integer zero-point)
+    inner = (wq.codes > 0) & (wq.codes < 15)
+    assert (np.abs(what - w)[inner] <= (sw[:, None] / 2 * (1 + 1e-4) * np.ones_like(what))[inner]).all()
+    assert (np.abs(what - w) <= sw[:, None] * 1.01).all()
+    np.testing.assert_array_equal(wq.colsum, wq.codes.astype(np.int64).sum(1))
+    np.testing.assert_allclose(wq.wsum, what.sum(1), rtol=1e-5, atol=1e-7)
+    # a symmetric range gives the mid zero-point 8 (the paper's symmetric weights as a special case)
+    ws = np.linspace(-0.9375, 0.9375, 256, dtype=np.float32).reshape(1, 256)   # step 0.125 is exact in bf16
+    assert oracle.quantize_weights(ws).zero[0] == 8.0
+
+
+# ---------------------------------------------------------------- integer GEMM and de-quantisation
+
+def test_int_gemm_brute_force_and_bounds():
+    rng = np.random.default_rng(30)
+    for (M, N, K) in [(1, 1, 2), (3, 5, 8), (7, 4, 34)]:
+        a = rng.integers(0, 16, (M, K)).astype(np.uint8)
+        w = rng.integers(0, 16, (N, K)).astype(np.uint8)
+        ref = [[sum(int(a[m, k]) * int(w[n, k]) for k in range(K)) for n in range(N)] for m in range(M)]
+        np.testing.assert_array_equal(oracle.int_gemm(a, w), np.array(ref, dtype=np.int32))
+    K = 4096
+    a = np.full((2, K), 15, np.uint8)
+    w = np.full((3, K), 15, np.uint8)
+    assert (oracle.int_gemm(a, w) == 225 * K).all()
+    # operand roles: [m, n] = a-row m . w-row n (not transposed)
+    a = rng.integers(0, 16, (2, 16)).astype(np.uint8)
+    w = rng.integers(0, 16, (5, 16)).astype(np.uint8)
+    assert oracle.int_gemm(a, w).shape == (2, 5)
+
+
+def test_int_gemm_blas_is_exact():
+    rng = np.random.default_rng(31)
+    a = rng.integers(0, 16, (96, 4096)).astype(np.uint8)
+    w = rng.integers(0, 16, (160, 4096)).astype(np.uint8)
+    np.testing.assert_array_equal(oracle.int_gemm_blas(a, w), oracle.int_gemm(a, w))
+
+
+def test_dequant_equals_product_of_dequantised_operands():
+    lay = si.make_tiny(24, 256, 40, seed=1)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    bc = oracle.channel_bias(x, 256)
+    wq = oracle.quantize_weights(w)
+    rng = np.random.default_rng(32)
+    lb = rng.standard_normal(40).astype(np.float32)
+    c = oracle.fused_bias(wq, bc, lb)
+    res = oracle.linear(x, 256, bc, None, 0.9, 0.9, wq, c)
+    xhat = oracle.dequantize_tokens(res.tq)
+    what = oracle.dequantize_weights(wq)
+    direct = xhat @ what.T + c.astype(np.float64)[None, :]
+    np.testing.assert_allclose(res.y, direct, rtol=1e-9, atol=1e-9)
+    # and the fused bias is W_hat . b^c + b
+    np.testing.assert_allclose(c, what @ bc.astype(np.float64) + lb, rtol=1e-6, atol=1e-7)
+
+
+def test_eq14_identity_without_quantisers():
+    """(r - b) W'^T + W' b = r W'^T = (x R)(W R)^T = x W^T  (bias and rotation applied, then undone)."""
+    rng = np.random.default_rng(33)
+    for n in (64, 56):
+        x = rng.standard_normal((6, n))
+        W = rng.standard_normal((9, n))
+        R = oracle.hadamard_matrix(n).astype(np.float64) / math.sqrt(n)
+        Wrot = W @ R
+        r = oracle.rotate_f64(x, n)
+        b = rng.standard_normal(n)
+        lhs = (r - b) @ Wrot.T + Wrot @ b
+        np.testing.assert_allclose(lhs, x @ W.T, atol=1e-10)
+        np.testing.assert_allclose(oracle.linear_full_precision(x, n, Wrot), x @ W.T, atol=1e-10)
+
+
+# ---------------------------------------------------------------- channel means (Sec. 3.2, Eq. 6)
+
+def test_variance_decomposition_and_bias_alignment():
+    lay = si.make_tiny(512, 256, 8, seed=2)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X)).astype(np.float64)
+    r = oracle.rotate_f64(x, 256)
+    for a in (x, r):                               # Eq. 6, population variances
+        total = a.var()
+        np.testing.assert_allclose(total, a.var(axis=0).mean() + a.mean(axis=0).var(), rtol=1e-10)
+    # first term is rotation invariant
+    np.testing.assert_allclose(r.var(axis=0).mean(), x.var(axis=0).mean(), rtol=1e-10)
+    bc = oracle.channel_bias(x, 256)
+    np.testing.assert_allclose(bc, r.mean(axis=0), rtol=1e-5, atol=1e-6)
+    v = r - bc.astype(np.float64)
+    assert v.mean(axis=0).var() < 1e-10 * r.mean(axis=0).var() + 1e-12     # Var(mu_j) removed
+    assert r.mean(axis=0).var() > 0.05                                      # it was there before
+
+
+def test_bias_correction_reduces_layer_error():
+    """The method's point: with misaligned channel means, subtracting b^c before the quantiser
+    lowers the output error of the W4A4 layer."""
+    lay = si.make_tiny(128, 512, 64, seed=3)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    wq = oracle.quantize_weights(w)
+    y_fp = oracle.rotate_f64(x, 512) @ oracle.dequantize_weights(wq).T
+    bc = oracle.channel_bias(x, 512)
+    with_b = oracle.linear(x, 512, bc, None, 1.0, 1.0, wq, oracle.fused_bias(wq, bc, None)).y
+    without = oracle.linear(x, 512, None, None, 1.0, 1.0, wq, None).y
+    e_with = ((with_b - y_fp) ** 2).mean()
+    e_without = ((without - y_fp) ** 2).mean()
+    assert e_with < 0.9 * e_without
+    assert e_with < 0.05 * (y_fp ** 2).mean()
+    # Eq. 5 and Eq. 6: rounding error scales with the total variance, and the bias removes the
+    # Var(mu_j) share of it -> the error ratio is about (mean channel variance) / (total variance)
+    r = oracle.rotate_f64(x, 512)
+    predicted = r.var(axis=0).mean() / r.var()
+    assert abs(e_with / e_without - predicted) < 0.2 * predicted
