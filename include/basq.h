@@ -1,0 +1,165 @@
+/*
+ * basq.h -- C ABI of the MI355X (gfx950) W4A4 rotated linear layer of BASE-Q.
+ *
+ * The layer (paper Sec. 4, Eq. 14 and Eq. 15; row-vector form, R orthogonal, W' = W R given):
+ *
+ *     Y = Q_a( s^a (X R) - b^c ) . Q_w(W')^T + c ,      c = W_hat b^c + b   ("fused bias")
+ *
+ *   R      normalised Hadamard rotation applied online to each block of rot_size channels
+ *          (Sec. 3.1: entries +-n^(-1/2); Sec. 4 "online rotations"), n = 2^t or 28 * 2^t
+ *   Q_a    per-token asymmetric uniform quantiser with lower bound z and step s (Eq. 4; "per-token
+ *          asymmetric dynamic quantization", Sec. 5), range [clip_lo*min, clip_hi*max]
+ *   Q_w    per-output-channel asymmetric INT4 weights: W_hat[n,k] = sw[n] * (q_w[n,k] - zp[n])
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless its comment says "host".
+ *     The library never frees caller memory; hot calls allocate nothing and never synchronise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work of a call
+ *     is enqueued on it in order.
+ *   - bf16 tensors are passed as void* (16-bit storage, round-to-nearest-even on output).
+ *   - Return value: BASQ_OK or a negative error code.  Arguments are validated on the host before
+ *     anything is launched; a failing call launches nothing.  basq_last_error() gives the text of
+ *     the calling thread's last error.
+ *   - Packed INT4 ("canonical") layout: byte j of a row holds code k = 2j in its low nibble and
+ *     code k = 2j+1 in its high nibble.
+ *   - Alignment: X, Aq, meta, Wq base pointers 16-byte aligned; K % 32 == 0; ldx % 8 == 0.  Y needs
+ *     only its natural 2-byte alignment and any ldy >= N.
+ */
+#ifndef BASQ_H
+#define BASQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BASQ_OK            0
+#define BASQ_EINVAL       (-1)  /* null pointer, bad shape, stride or alignment */
+#define BASQ_EUNSUPPORTED (-2)  /* valid request the library does not implement (bits != 4, ...) */
+#define BASQ_EWORKSPACE   (-3)  /* workspace too small */
+#define BASQ_EHIP         (-4)  /* a HIP call or launch failed */
+
+#define BASQ_W_CANONICAL 0      /* Wq is [N, K/2] in the canonical packed layout */
+
+/* Per-token quantisation record written by basq_rotate_quant and read by basq_w4a4_gemm.
+ * x_hat[m,k] = scale * q[m,k] + lo   (Eq. 4 with z = lo);  rowsum = sum_k q[m,k]. */
+typedef struct {
+    float   scale;
+    float   lo;
+    int32_t rowsum;
+    int32_t reserved;
+} basq_tokmeta;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int basq_version(void);
+
+/* Text of the calling thread's most recent error ("" if none).  Host pointer, valid until the
+ * thread's next failing call. */
+const char* basq_last_error(void);
+
+/*
+ * Online rotation + bias + per-token quantisation (Sec. 3.1 rotation; Eq. 14 bias; Eq. 15 scale;
+ * Eq. 4 quantiser; Fig. 6 "fused quant kernel").  For each token m:
+ *
+ *     r      = X[m,:] . (H_n / sqrt(n))     blockwise over K/rot_size blocks, fp32
+ *     v_k    = r_k - bias_k                 (act_scale == NULL)
+ *     v_k    = fma(r_k, act_scale_k, -bias_k)
+ *     lo     = clip_lo * min_k v_k ;  hi = clip_hi * max_k v_k
+ *     s      = (hi - lo) / 15  (1 if not a positive finite number) ;  inv = 1/s ;  nlo = -(lo*inv)
+ *     q_k    = rint(min(max(fma(v_k, inv, nlo), 0), 15))        round-half-to-even, NaN -> 0
+ *
+ *   X          bf16 [M, ldx], row m at X + m*ldx, ldx >= K
+ *   rot_size   n; K % n == 0; n = 2^t (t >= 1) or 28 * 2^t (t >= 1).  For n = 28 * 2^t the matrix is
+ *              H_28 (x) H_(2^t) with the Paley type-I H_28 over GF(27) (see basq_hadamard28) and
+ *              channel index k = i * 2^t + j, i the H_28 index.
+ *   bias       fp32 [K] b^c in the rotated basis, or NULL (= 0)
+ *   act_scale  fp32 [K] s^a, or NULL (= 1)
+ *   bits       must be 4 (else BASQ_EUNSUPPORTED)
+ *   group_size 0 or K: one range per token.  Other values: BASQ_EUNSUPPORTED.
+ *   Aq         out, uint8 [M, K/2] canonical packed codes
+ *   meta       out, [M]
+ *   rot_out    out, optional debug dump of r, fp32 [M, K]; NULL to skip
+ * M == 0 is valid and does nothing.
+ */
+int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
+                      const float* bias, const float* act_scale,
+                      float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                      uint8_t* Aq, basq_tokmeta* meta, float* rot_out, void* stream);
+
+/*
+ * INT4 x INT4 GEMM with INT32 accumulation and fused de-quantisation (Sec. 5.2; Fig. 6
+ * "de-quantisation" with the bias folded in; Eq. 14 fused bias):
+ *
+ *     ACC[m,n] = sum_k q_a[m,k] * q_w[n,k]
+ *     Y[m,n]   = bf16( s_m * sw_n * (ACC[m,n] - zp_n * rowsum_m) + lo_m * w_sum_n + out_bias_n )
+ *
+ *   Aq, meta   as written by basq_rotate_quant, [M, K/2] and [M]
+ *   Wq         uint8 [N, K/2]; w_layout must be BASQ_W_CANONICAL
+ *   w_scale    bf16 [N] sw;  w_zero  bf16 [N] zp in code units (any real value)
+ *   w_sum      fp32 [N] = sw_n * (sum_k q_w[n,k] - K * zp_n) = sum_k W_hat[n,k]
+ *   out_bias   fp32 [N] c, or NULL (= 0)
+ *   Y          out, bf16 [M, ldy], ldy >= N
+ *   acc_out    out, optional debug dump of ACC, int32 [M, N]; NULL to skip
+ * Any M >= 0, N >= 1; small M (decode) takes a weight-streaming path, same results.
+ */
+int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K,
+                   const uint8_t* Wq, int32_t N, int32_t w_layout,
+                   const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
+                   void* Y, int64_t ldy, int32_t* acc_out, void* stream);
+
+/* Bytes of workspace basq_linear_fused needs for this shape (activation codes + token records). */
+size_t basq_workspace_bytes(int64_t M, int32_t K, int32_t N);
+
+/*
+ * The whole layer in one call: basq_rotate_quant then basq_w4a4_gemm on `stream`, the codes and
+ * token records living in `workspace` (256-byte aligned, >= basq_workspace_bytes(M, K, N), else
+ * BASQ_EWORKSPACE).  Arguments as in the two calls above.
+ */
+int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
+                      const float* bias, const float* act_scale,
+                      float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                      const uint8_t* Wq, int32_t N, int32_t w_layout,
+                      const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
+                      void* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- offline helpers (not on the timed path) --------------------------------------------- */
+
+/*
+ * Round-to-nearest per-output-channel asymmetric INT4 quantisation of rotated-basis weights
+ * (weights are quantised per channel, Sec. 5 "Deployment Details"; asymmetric with a bf16
+ * zero-point per the workload definition).  Per row n, every operation one fp32 operation:
+ *     lo, hi = min_k W', max_k W' ;  sw = bf16((hi - lo)/15)  (1 if not positive finite)
+ *     zp = clamp(rint(-lo/sw), 0, 15) ;  q = clamp(rint(W'/sw) + zp, 0, 15)
+ *     w_sum = fp32( double(sw) * (sum_k q - K*zp) )
+ *   W_rot bf16 [N, ldw];  outputs Wq [N, K/2] canonical, w_scale bf16 [N], w_zero bf16 [N], w_sum fp32 [N].
+ */
+int basq_quantize_weights(const void* W_rot, int32_t N, int32_t K, int64_t ldw,
+                          uint8_t* Wq, void* w_scale, void* w_zero, float* w_sum, void* stream);
+
+/*
+ * Fused bias of Eq. 14 from the dequantised weights:  out_bias[n] = sum_k W_hat[n,k] * bias[k]
+ * + layer_bias[n], accumulated in fp64, stored fp32.  bias (b^c, fp32 [K]) and layer_bias
+ * (fp32 [N]) may each be NULL (= 0).
+ */
+int basq_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const void* w_scale, const void* w_zero,
+                    const float* bias, const float* layer_bias, float* out_bias, void* stream);
+
+/*
+ * Channel bias calibration (Sec. 3.2: the bias cancels the per-channel means after rotation):
+ *     bias_out[k] = mean_m ( s^a_k * r[m,k] ),  r the rotated calibration tokens; fp64 mean, fp32 out.
+ * workspace: >= M*K*4 bytes (holds r), else BASQ_EWORKSPACE.
+ */
+int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
+                        const float* act_scale, float* bias_out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The 28 x 28 matrix of +-1 used for rot_size = 28 * 2^t, row-major into a HOST buffer of 784
+ * int8 (Paley type-I construction over GF(27) = GF(3)[t]/(t^3 + 2t + 1)). */
+int basq_hadamard28(int8_t* out_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BASQ_H */

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of libbasq.so: same names as the C ABI (include/basq.h), torch tensors in,
+argument marshalling only.  Every step of the layer runs in the HIP kernels; there is no CPU
+fallback -- if the library is missing or a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libbasq.so")
+
+BASQ_OK = 0
+BASQ_EINVAL = -1
+BASQ_EUNSUPPORTED = -2
+BASQ_EWORKSPACE = -3
+BASQ_EHIP = -4
+BASQ_W_CANONICAL = 0
+
+EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
+           "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_hadamard28"]
+
+
+class BasqError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libbasq error {code}: {text}")
+        self.code = code
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libbasq.so (built in-tree by paper_2506_15689_amd.build.build_lib)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_15689_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, i32, f32 = c.c_void_p, c.c_int64, c.c_int32, c.c_float
+    lib.basq_version.restype = c.c_int
+    lib.basq_version.argtypes = []
+    lib.basq_last_error.restype = c.c_char_p
+    lib.basq_last_error.argtypes = []
+    lib.basq_rotate_quant.restype = c.c_int
+    lib.basq_rotate_quant.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32, vp, vp, vp, vp]
+    lib.basq_w4a4_gemm.restype = c.c_int
+    lib.basq_w4a4_gemm.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
+    lib.basq_workspace_bytes.restype = c.c_size_t
+    lib.basq_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.basq_linear_fused.restype = c.c_int
+    lib.basq_linear_fused.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32,
+                                      vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, c.c_size_t, vp]
+    lib.basq_quantize_weights.restype = c.c_int
+    lib.basq_quantize_weights.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp]
+    lib.basq_fused_bias.restype = c.c_int
+    lib.basq_fused_bias.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.basq_calibrate_bias.restype = c.c_int
+    lib.basq_calibrate_bias.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, c.c_size_t, vp]
+    lib.basq_hadamard28.restype = c.c_int
+    lib.basq_hadamard28.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc: int) -> None:
+    if rc != BASQ_OK:
+        raise BasqError(rc, load().basq_last_error().decode("utf-8", "replace"))
+
+
+def basq_version() -> int:
+    return int(load().basq_version())
+
+
+def basq_last_error() -> str:
+    return load().basq_last_error().decode("utf-8", "replace")
+
+
+def basq_hadamard28() -> torch.Tensor:
+    out = torch.empty(28 * 28, dtype=torch.int8)
+    _check(load().basq_hadamard28(ctypes.c_void_p(out.data_ptr())))
+    return out.view(28, 28)
+
+
+def basq_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(load().basq_workspace_bytes(M, K, N))
+
+
+def basq_rotate_quant(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tensor], act_scale: Optional[torch.Tensor],
+                      clip_lo: float, clip_hi: float, Aq: torch.Tensor, meta: torch.Tensor,
+                      rot_out: Optional[torch.Tensor] = None, *, bits: int = 4, group_size: int = 0,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+    """X bf16 [M, K] (row stride X.stride(0)); Aq uint8 [M, K/2]; meta int32 [M, 4] (16-byte records)."""
+    M, K = X.shape
+    _check(load().basq_rotate_quant(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
+                                    clip_lo, clip_hi, bits, group_size, _p(Aq), _p(meta), _p(rot_out),
+                                    _stream(stream)))
+
+
+def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
+                   w_zero: torch.Tensor, w_sum: torch.Tensor, out_bias: Optional[torch.Tensor], Y: torch.Tensor,
+                   acc_out: Optional[torch.Tensor] = None, *, w_layout: int = BASQ_W_CANONICAL,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    M, KB = Aq.shape
+    N = Wq.shape[0]
+    _check(load().basq_w4a4_gemm(_p(Aq), _p(meta), M, KB * 2, _p(Wq), N, w_layout, _p(w_scale), _p(w_zero),
+                                 _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _p(acc_out),
+                                 _stream(stream)))
+
+
+def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tensor],
+                      act_scale: Optional[torch.Tensor], clip_lo: float, clip_hi: float, Wq: torch.Tensor,
+                      w_scale: torch.Tensor, w_zero: torch.Tensor, w_sum: torch.Tensor,
+                      out_bias: Optional[torch.Tensor], Y: torch.Tensor, workspace: torch.Tensor, *,
+                      bits: int = 4, group_size: int = 0, w_layout: int = BASQ_W_CANONICAL,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+    M, K = X.shape
+    N = Wq.shape[0]
+    _check(load().basq_linear_fused(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
+                                    clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout, _p(w_scale),
+                                    _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
+                                    _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def basq_quantize_weights(W_rot: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, w_zero: torch.Tensor,
+                          w_sum: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    N, K = W_rot.shape
+    _check(load().basq_quantize_weights(_p(W_rot), N, K, W_rot.stride(0), _p(Wq), _p(w_scale), _p(w_zero),
+                                        _p(w_sum), _stream(stream)))
+
+
+def basq_fused_bias(Wq: torch.Tensor, w_scale: torch.Tensor, w_zero: torch.Tensor, bias: Optional[torch.Tensor],
+                    layer_bias: Optional[torch.Tensor], out_bias: torch.Tensor, *,
+                    stream: Optional[torch.cuda.Stream] = None) -> None:
+    N, KB = Wq.shape
+    _check(load().basq_fused_bias(_p(Wq), N, KB * 2, _p(w_scale), _p(w_zero), _p(bias), _p(layer_bias),
+                                  _p(out_bias), _stream(stream)))
+
+
+def basq_calibrate_bias(X: torch.Tensor, rot_size: int, act_scale: Optional[torch.Tensor], bias_out: torch.Tensor,
+                        workspace: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    M, K = X.shape
+    _check(load().basq_calibrate_bias(_p(X), M, K, X.stride(0), rot_size, _p(act_scale), _p(bias_out),
+                                      _p(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)))
+
+
+# ---- allocation helpers (device memory only; no arithmetic) ----------------------------------
+
+def alloc_activation_buffers(M: int, K: int, device="cuda") -> Tuple[torch.Tensor, torch.Tensor]:
+    """(Aq uint8 [M, K/2], meta int32 [M, 4]) for basq_rotate_quant / basq_w4a4_gemm."""
+    return (torch.empty((M, K // 2), dtype=torch.uint8, device=device),
+            torch.empty((M, 4), dtype=torch.int32, device=device))
+
+
+def alloc_weight_buffers(N: int, K: int, device="cuda"):
+    """(Wq uint8 [N, K/2], w_scale bf16 [N], w_zero bf16 [N], w_sum fp32 [N])."""
+    return (torch.empty((N, K // 2), dtype=torch.uint8, device=device),
+            torch.empty(N, dtype=torch.bfloat16, device=device),
+            torch.empty(N, dtype=torch.bfloat16, device=device),
+            torch.empty(N, dtype=torch.float32, device=device))

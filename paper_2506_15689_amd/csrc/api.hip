@@ -1,0 +1,205 @@
+// C-ABI layer of libbasq: argument validation, error text, dispatch.  No arithmetic here.
+#include "basq_internal.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+
+namespace basq {
+
+namespace {
+thread_local char g_err[512] = "";
+}
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return BASQ_OK;
+    return fail(BASQ_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// n = 2^t (t >= 1) or 28 * 2^t (t >= 1); fills the Sylvester factor and the H_28 flag.
+bool split_rot_size(int32_t n, int32_t* pow2, int32_t* has28) {
+    if (n < 2) return false;
+    if (is_pow2(n)) { *pow2 = n; *has28 = 0; return true; }
+    if (n % 28 == 0 && is_pow2(n / 28) && n / 28 >= 2) { *pow2 = n / 28; *has28 = 1; return true; }
+    return false;
+}
+
+int validate_rotate(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, int32_t bits,
+                    int32_t group_size, float clip_lo, float clip_hi, int32_t* pow2, int32_t* has28) {
+    if (M < 0) return fail(BASQ_EINVAL, "M must be >= 0 (got %lld)", (long long)M);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    if (K > 32768) return fail(BASQ_EUNSUPPORTED, "K up to 32768 is supported (got %d)", K);
+    if (ldx < K || ldx % 8 != 0) return fail(BASQ_EINVAL, "ldx must be >= K and a multiple of 8 (got %lld)", (long long)ldx);
+    if (!split_rot_size(rot_size, pow2, has28))
+        return fail(BASQ_EUNSUPPORTED, "rot_size must be 2^t or 28*2^t with t >= 1 (got %d)", rot_size);
+    if (K % rot_size != 0) return fail(BASQ_EINVAL, "K (%d) must be a multiple of rot_size (%d)", K, rot_size);
+    if (bits != 4) return fail(BASQ_EUNSUPPORTED, "only bits == 4 is implemented (got %d)", bits);
+    if (group_size != 0 && group_size != K)
+        return fail(BASQ_EUNSUPPORTED, "only per-token ranges are implemented: group_size must be 0 or K (got %d)", group_size);
+    if (!(clip_lo > 0.0f) || !(clip_hi > 0.0f) || !(clip_lo <= 1.0f) || !(clip_hi <= 1.0f))
+        return fail(BASQ_EINVAL, "clip ratios must be in (0, 1] (got %g, %g)", (double)clip_lo, (double)clip_hi);
+    if (M > 0 && X == nullptr) return fail(BASQ_EINVAL, "X is null");
+    if (!aligned16(X)) return fail(BASQ_EINVAL, "X must be 16-byte aligned");
+    return BASQ_OK;
+}
+
+int validate_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, const uint8_t* Wq, int32_t N,
+                  int32_t w_layout, const void* w_scale, const void* w_zero, const float* w_sum, const void* Y,
+                  int64_t ldy) {
+    if (M < 0) return fail(BASQ_EINVAL, "M must be >= 0 (got %lld)", (long long)M);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (w_layout != BASQ_W_CANONICAL) return fail(BASQ_EUNSUPPORTED, "unknown w_layout %d", w_layout);
+    if (ldy < N) return fail(BASQ_EINVAL, "ldy must be >= N (got %lld)", (long long)ldy);
+    if (!Wq || !w_scale || !w_zero || !w_sum) return fail(BASQ_EINVAL, "a weight-side pointer is null");
+    if (M > 0 && (!Aq || !meta || !Y)) return fail(BASQ_EINVAL, "an activation-side pointer is null");
+    if (!aligned16(Aq) || !aligned16(Wq) || !aligned16(meta))
+        return fail(BASQ_EINVAL, "Aq, meta and Wq must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(Y) & 1u) != 0) return fail(BASQ_EINVAL, "Y must be 2-byte aligned");
+    if ((int64_t)K * 225 > 0x7FFFFFFFll) return fail(BASQ_EUNSUPPORTED, "K too large for INT32 accumulation");
+    return BASQ_OK;
+}
+
+int run_gemm(const GemmArgs& g, hipStream_t s) {
+    if (g.M <= 16 && g.K % 128 == 0) return launch_gemv_decode(g, s);
+    return launch_gemm_prefill(g, s);
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+}  // namespace basq
+
+using namespace basq;
+
+extern "C" {
+
+int basq_version(void) { return 100; }
+
+const char* basq_last_error(void) { return g_err; }
+
+int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
+                      const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                      uint8_t* Aq, basq_tokmeta* meta, float* rot_out, void* stream) {
+    RotateQuantArgs a{};
+    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
+    if (rc != BASQ_OK) return rc;
+    if (M > 0 && (!Aq || !meta)) return fail(BASQ_EINVAL, "Aq or meta is null");
+    if (!aligned16(Aq) || !aligned16(meta) || !aligned16(rot_out))
+        return fail(BASQ_EINVAL, "Aq, meta and rot_out must be 16-byte aligned");
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
+    a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
+    a.Aq = Aq; a.meta = meta; a.rot_out = rot_out;
+    return launch_rotate_quant(a, static_cast<hipStream_t>(stream));
+}
+
+int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, const uint8_t* Wq, int32_t N,
+                   int32_t w_layout, const void* w_scale, const void* w_zero, const float* w_sum,
+                   const float* out_bias, void* Y, int64_t ldy, int32_t* acc_out, void* stream) {
+    int rc = validate_gemm(Aq, meta, M, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
+    if (rc != BASQ_OK) return rc;
+    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, acc_out};
+    return run_gemm(g, static_cast<hipStream_t>(stream));
+}
+
+size_t basq_workspace_bytes(int64_t M, int32_t K, int32_t N) {
+    (void)N;
+    if (M < 0 || K <= 0) return 0;
+    return align_up((size_t)M * (size_t)(K / 2), 256) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
+}
+
+int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
+                      const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                      const uint8_t* Wq, int32_t N, int32_t w_layout, const void* w_scale, const void* w_zero,
+                      const float* w_sum, const float* out_bias, void* Y, int64_t ldy, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    RotateQuantArgs a{};
+    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
+    if (rc != BASQ_OK) return rc;
+    if (M == 0) {
+        return validate_gemm(nullptr, nullptr, 0, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
+    }
+    if (!workspace) return fail(BASQ_EINVAL, "workspace is null");
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(BASQ_EINVAL, "workspace must be 256-byte aligned");
+    const size_t need = basq_workspace_bytes(M, K, N);
+    if (workspace_bytes < need)
+        return fail(BASQ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    uint8_t* Aq = static_cast<uint8_t*>(workspace);
+    basq_tokmeta* meta = reinterpret_cast<basq_tokmeta*>(Aq + align_up((size_t)M * (size_t)(K / 2), 256));
+    rc = validate_gemm(Aq, meta, M, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
+    if (rc != BASQ_OK) return rc;
+
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
+    a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
+    a.Aq = Aq; a.meta = meta; a.rot_out = nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = launch_rotate_quant(a, s);
+    if (rc != BASQ_OK) return rc;
+    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr};
+    return run_gemm(g, s);
+}
+
+int basq_quantize_weights(const void* W_rot, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq, void* w_scale,
+                          void* w_zero, float* w_sum, void* stream) {
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    if (ldw < K) return fail(BASQ_EINVAL, "ldw must be >= K");
+    if (!W_rot || !Wq || !w_scale || !w_zero || !w_sum) return fail(BASQ_EINVAL, "a pointer is null");
+    return launch_quantize_weights(static_cast<const uint16_t*>(W_rot), N, K, ldw, Wq, static_cast<uint16_t*>(w_scale),
+                                   static_cast<uint16_t*>(w_zero), w_sum, static_cast<hipStream_t>(stream));
+}
+
+int basq_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const void* w_scale, const void* w_zero,
+                    const float* bias, const float* layer_bias, float* out_bias, void* stream) {
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    if (!Wq || !w_scale || !w_zero || !out_bias) return fail(BASQ_EINVAL, "a pointer is null");
+    return launch_fused_bias(Wq, N, K, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+                             bias, layer_bias, out_bias, static_cast<hipStream_t>(stream));
+}
+
+int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* act_scale,
+                        float* bias_out, void* workspace, size_t workspace_bytes, void* stream) {
+    RotateQuantArgs a{};
+    int rc = validate_rotate(X, M, K, ldx, rot_size, 4, 0, 1.0f, 1.0f, &a.pow2, &a.has28);
+    if (rc != BASQ_OK) return rc;
+    if (M < 1) return fail(BASQ_EINVAL, "calibration needs at least one token");
+    if (!bias_out || !workspace) return fail(BASQ_EINVAL, "a pointer is null");
+    if (!aligned16(workspace)) return fail(BASQ_EINVAL, "workspace must be 16-byte aligned");
+    const size_t need = (size_t)M * (size_t)K * sizeof(float);
+    if (workspace_bytes < need)
+        return fail(BASQ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
+    a.clip_lo = a.clip_hi = 1.0f;
+    a.rot_out = static_cast<float*>(workspace);      // rotation-only mode: Aq/meta stay null
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = launch_rotate_quant(a, s);
+    if (rc != BASQ_OK) return rc;
+    return launch_column_mean(a.rot_out, M, K, act_scale, bias_out, s);
+}
+
+int basq_hadamard28(int8_t* out_host) {
+    if (!out_host) return fail(BASQ_EINVAL, "out_host is null");
+    const int8_t* h = hadamard28_host();
+    for (int i = 0; i < 28 * 28; ++i) out_host[i] = h[i];
+    return BASQ_OK;
+}
+
+}  // extern "C"

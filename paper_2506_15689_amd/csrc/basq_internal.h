@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP translation units of libbasq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/basq.h"
+
+namespace basq {
+
+// ---- error reporting (api.hip) ---------------------------------------------------------------
+int fail(int code, const char* fmt, ...);
+int check_hip(hipError_t e, const char* what);
+
+// ---- launchers; every argument already validated by the C-ABI layer --------------------------
+struct RotateQuantArgs {
+    const uint16_t* X;        // bf16 bits
+    int64_t M;
+    int32_t K;
+    int64_t ldx;
+    int32_t rot_size;         // n
+    int32_t pow2;             // Sylvester factor of n (n itself, or n/28)
+    int32_t has28;            // 1 if n = 28 * pow2
+    const float* bias;
+    const float* act_scale;
+    float clip_lo, clip_hi;
+    uint8_t* Aq;              // may be null in rot-only mode
+    basq_tokmeta* meta;       // may be null in rot-only mode
+    float* rot_out;           // optional
+};
+int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s);
+
+struct GemmArgs {
+    const uint8_t* Aq;
+    const basq_tokmeta* meta;
+    int64_t M;
+    int32_t K;
+    const uint8_t* Wq;
+    int32_t N;
+    const uint16_t* w_scale;  // bf16 bits
+    const uint16_t* w_zero;
+    const float* w_sum;
+    const float* out_bias;
+    uint16_t* Y;
+    int64_t ldy;
+    int32_t* acc_out;
+};
+int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
+int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
+
+int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq,
+                            uint16_t* w_scale, uint16_t* w_zero, float* w_sum, hipStream_t s);
+int launch_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const uint16_t* w_scale, const uint16_t* w_zero,
+                      const float* bias, const float* layer_bias, float* out_bias, hipStream_t s);
+int launch_column_mean(const float* r, int64_t M, int32_t K, const float* act_scale, float* out, hipStream_t s);
+
+// 28 x 28 Paley type-I matrix, row-major, built on the host at first use (hadamard28.hip).
+const int8_t* hadamard28_host();
+
+// ---- small device helpers --------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16 bits, round-half-to-even, NaN kept quiet.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+}  // namespace basq

@@ -1,0 +1,153 @@
+"""Shared plumbing of the GPU parity tests: builds one case (oracle-side numpy arrays and the
+device tensors made from the SAME bits), runs the HIP path through the binding, and compares
+at the three levels the acceptance criteria name:
+
+  (i)   the GPU's fp32 rotation output is fed to the oracle's quantiser and integer GEMM:
+        codes, token records and INT32 accumulators must match bit for bit;
+  (ii)  the oracle's whole path from X: bf16 outputs within 2e-2 of max|ref|;
+  (iii) codes from the oracle's own (fp64) rotation vs the GPU's: at most 1e-4 of them differ,
+        each by one code (fp32 summation order in the rotation is the only source).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2506_15689_amd import binding as B
+from paper_2506_15689_amd import synth_inputs as si
+
+Y_TOL = 2e-2
+FLIP_TOL = 1e-4
+
+
+@dataclass
+class Case:
+    M: int
+    K: int
+    N: int
+    rot_size: int
+    clip_lo: float
+    clip_hi: float
+    x: np.ndarray                 # fp32 [M, K] (exact bf16 values)
+    bias: Optional[np.ndarray]    # fp32 [K]
+    act_scale: Optional[np.ndarray]
+    wq: oracle.WeightQuant
+    c: Optional[np.ndarray]       # fp32 [N]
+    X_t: torch.Tensor             # bf16 CPU tensor
+
+
+def make_case(lay: si.LayerInputs, *, rot_size: Optional[int] = None, clip_lo: Optional[float] = None,
+              clip_hi: Optional[float] = None, act_scale: Optional[np.ndarray] = None, use_bias: bool = True,
+              use_out_bias: bool = True) -> Case:
+    cfg = lay.cfg
+    M, K = lay.X.shape
+    N = lay.W_rot.shape[0]
+    n = cfg.rot_size if rot_size is None else rot_size
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    bias = None
+    if use_bias:
+        xc = oracle.bf16_to_f32(si.bf16_bits(lay.X_calib))
+        bias = oracle.channel_bias(xc, n)
+        if act_scale is not None:
+            bias = (bias.astype(np.float64) * act_scale.astype(np.float64)).astype(np.float32)
+    wq = oracle.quantize_weights(w)
+    c = None
+    if use_out_bias:
+        lb = None if lay.layer_bias is None else lay.layer_bias.numpy()
+        c = oracle.fused_bias(wq, bias, lb)
+    return Case(M, K, N, n, cfg.clip if clip_lo is None else clip_lo, cfg.clip if clip_hi is None else clip_hi,
+                x, bias, act_scale, wq, c, lay.X)
+
+
+@dataclass
+class DeviceCase:
+    X: torch.Tensor
+    bias: Optional[torch.Tensor]
+    act_scale: Optional[torch.Tensor]
+    Wq: torch.Tensor
+    w_scale: torch.Tensor
+    w_zero: torch.Tensor
+    w_sum: torch.Tensor
+    out_bias: Optional[torch.Tensor]
+
+
+def to_device(case: Case, dev="cuda") -> DeviceCase:
+    f = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    return DeviceCase(case.X_t.to(dev), f(case.bias), f(case.act_scale), f(oracle.pack_codes(case.wq.codes)),
+                      si.bits_to_bf16(case.wq.scale_bits).to(dev), si.bits_to_bf16(case.wq.zero_bits).to(dev),
+                      f(case.wq.wsum), f(case.c))
+
+
+@dataclass
+class GpuResult:
+    rot: np.ndarray        # fp32 [M, K]
+    codes: np.ndarray      # uint8 [M, K]
+    scale: np.ndarray      # fp32 [M]
+    lo: np.ndarray         # fp32 [M]
+    rowsum: np.ndarray     # int32 [M]
+    acc: np.ndarray        # int32 [M, N]
+    y_bits: np.ndarray     # uint16 [M, N]
+    y_fused_bits: np.ndarray
+
+
+def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
+    dev = d.X.device
+    M, K, N = case.M, case.K, case.N
+    Aq, meta = B.alloc_activation_buffers(M, K, dev)
+    rot = torch.empty((M, K), dtype=torch.float32, device=dev)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+    Yf = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+    acc = torch.full((M, N), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(B.basq_workspace_bytes(M, K, N), 256), dtype=torch.uint8, device=dev)
+    B.basq_rotate_quant(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, Aq, meta, rot)
+    B.basq_w4a4_gemm(Aq, meta, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Y, acc)
+    B.basq_linear_fused(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, d.Wq, d.w_scale,
+                        d.w_zero, d.w_sum, d.out_bias, Yf, ws)
+    torch.cuda.synchronize()
+    meta_h = meta.cpu().numpy()
+    return GpuResult(rot.cpu().numpy(), oracle.unpack_codes(Aq.cpu().numpy()),
+                     meta_h[:, 0].copy().view(np.float32), meta_h[:, 1].copy().view(np.float32),
+                     meta_h[:, 2].copy(), acc.cpu().numpy(), si.bf16_bits(Y.cpu()), si.bf16_bits(Yf.cpu()))
+
+
+def check_parity(case: Case, g: GpuResult, *, rows: Optional[np.ndarray] = None, use_blas_gemm: bool = False,
+                 y_tol: float = Y_TOL, flip_tol: float = FLIP_TOL) -> dict:
+    """Compare the GPU result with the oracle.  ``rows``: check only these token rows (full-size
+    cases where the oracle would take too long on everything); the GPU still ran all rows."""
+    sel = np.arange(case.M) if rows is None else np.asarray(rows)
+    x = case.x[sel]
+    # level (i): oracle on the GPU's rotation output
+    ref_i = oracle.linear(x, case.rot_size, case.bias, case.act_scale, case.clip_lo, case.clip_hi, case.wq,
+                          case.c, r=g.rot[sel], use_blas_gemm=use_blas_gemm)
+    np.testing.assert_array_equal(g.codes[sel], ref_i.tq.codes, err_msg="activation codes (level i)")
+    np.testing.assert_array_equal(g.scale[sel].view(np.uint32), ref_i.tq.scale[:, 0].view(np.uint32), err_msg="scale bits")
+    np.testing.assert_array_equal(g.lo[sel].view(np.uint32), ref_i.tq.lo[:, 0].view(np.uint32), err_msg="lo bits")
+    np.testing.assert_array_equal(g.rowsum[sel], ref_i.tq.rowsum[:, 0], err_msg="row sums")
+    np.testing.assert_array_equal(g.acc[sel], ref_i.acc, err_msg="INT32 accumulators (level i)")
+    # the one-call entry point runs the same kernels: identical bits
+    np.testing.assert_array_equal(g.y_fused_bits, g.y_bits, err_msg="basq_linear_fused vs two calls")
+
+    # levels (ii) and (iii): oracle from X with its own rotation
+    ref = oracle.linear(x, case.rot_size, case.bias, case.act_scale, case.clip_lo, case.clip_hi, case.wq, case.c,
+                        use_blas_gemm=use_blas_gemm)
+    rot_err = float(np.abs(g.rot[sel].astype(np.float64) - ref.r.astype(np.float64)).max())
+    rot_scale = float(np.abs(ref.r).max())
+    assert rot_err <= 2e-5 * max(rot_scale, 1.0), f"rotation error {rot_err} (max |r| {rot_scale})"
+    d = g.codes[sel].astype(np.int32) - ref.tq.codes.astype(np.int32)
+    flips = d != 0
+    flip_rate = float(flips.mean()) if flips.size else 0.0
+    assert flip_rate <= flip_tol, f"code flip rate {flip_rate}"
+    assert (np.abs(d[flips]) == 1).all(), "a code differs by more than one step"
+    y = oracle.bf16_to_f32(g.y_bits[sel]).astype(np.float64)
+    denom = float(np.abs(ref.y).max()) if ref.y.size else 1.0
+    y_err = float(np.abs(y - ref.y).max() / denom) if ref.y.size else 0.0
+    assert y_err <= y_tol, f"output error {y_err} of max|ref|"
+    # and against the level-(i) reference the output differs only by fp32 epilogue rounding + bf16
+    y_i = float(np.abs(y - ref_i.y).max() / denom) if ref.y.size else 0.0
+    assert y_i <= 2 ** -7, f"epilogue error {y_i} of max|ref| on identical accumulators"
+    return {"flip_rate": flip_rate, "y_err": y_err, "y_err_same_acc": y_i, "rot_err": rot_err}

@@ -1,0 +1,127 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and turns
+bad arguments into error codes before anything would be launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_15689_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2506_15689_amd import build
+        build.build_lib(verbose=False)
+    return B.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "basq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(basq_[a-z0-9_]+)\s*\(", header))
+    assert {"basq_rotate_quant", "basq_w4a4_gemm", "basq_linear_fused"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in basq.h but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+def test_version_and_error_text(lib):
+    assert B.basq_version() >= 100
+    rc = lib.basq_rotate_quant(None, 4, 100, 100, 64, None, None, 0.9, 0.9, 4, 0, None, None, None, None)
+    assert rc == B.BASQ_EINVAL and "multiple of 32" in B.basq_last_error()
+
+
+FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fails first
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(M=-1), B.BASQ_EINVAL),
+    (dict(K=0), B.BASQ_EINVAL),
+    (dict(K=48), B.BASQ_EINVAL),
+    (dict(ldx=1016), B.BASQ_EINVAL),
+    (dict(ldx=1028), B.BASQ_EINVAL),
+    (dict(rot=1000), B.BASQ_EUNSUPPORTED),
+    (dict(rot=28), B.BASQ_EUNSUPPORTED),
+    (dict(rot=768), B.BASQ_EUNSUPPORTED),
+    (dict(K=1024, rot=512 * 3), B.BASQ_EUNSUPPORTED),
+    (dict(K=1024 + 512, ldx=2048, rot=1024), B.BASQ_EINVAL),
+    (dict(bits=8), B.BASQ_EUNSUPPORTED),
+    (dict(bits=3), B.BASQ_EUNSUPPORTED),
+    (dict(group=128), B.BASQ_EUNSUPPORTED),
+    (dict(clip_lo=0.0), B.BASQ_EINVAL),
+    (dict(clip_hi=1.5), B.BASQ_EINVAL),
+    (dict(clip_lo=float("nan")), B.BASQ_EINVAL),
+    (dict(X=None), B.BASQ_EINVAL),
+    (dict(X=ctypes.c_void_p(0x1008)), B.BASQ_EINVAL),
+    (dict(Aq=None), B.BASQ_EINVAL),
+    (dict(meta=None), B.BASQ_EINVAL),
+    (dict(K=65536, ldx=65536, rot=65536), B.BASQ_EUNSUPPORTED),
+])
+def test_rotate_quant_rejects_bad_arguments(lib, kw, code):
+    a = dict(X=FAKE, M=4, K=1024, ldx=1024, rot=1024, bias=None, sa=None, clip_lo=0.9, clip_hi=0.9, bits=4,
+             group=0, Aq=FAKE, meta=FAKE, rot_out=None)
+    a.update(kw)
+    rc = lib.basq_rotate_quant(a["X"], a["M"], a["K"], a["ldx"], a["rot"], a["bias"], a["sa"], a["clip_lo"],
+                               a["clip_hi"], a["bits"], a["group"], a["Aq"], a["meta"], a["rot_out"], None)
+    assert rc == code, B.basq_last_error()
+    assert B.basq_last_error() != ""
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(M=-2), B.BASQ_EINVAL),
+    (dict(K=100), B.BASQ_EINVAL),
+    (dict(N=0), B.BASQ_EINVAL),
+    (dict(layout=7), B.BASQ_EUNSUPPORTED),
+    (dict(ldy=100), B.BASQ_EINVAL),
+    (dict(Wq=None), B.BASQ_EINVAL),
+    (dict(w_scale=None), B.BASQ_EINVAL),
+    (dict(w_zero=None), B.BASQ_EINVAL),
+    (dict(w_sum=None), B.BASQ_EINVAL),
+    (dict(Aq=None), B.BASQ_EINVAL),
+    (dict(Y=None), B.BASQ_EINVAL),
+    (dict(Aq=ctypes.c_void_p(0x1004)), B.BASQ_EINVAL),
+    (dict(Y=ctypes.c_void_p(0x1001)), B.BASQ_EINVAL),
+])
+def test_gemm_rejects_bad_arguments(lib, kw, code):
+    a = dict(Aq=FAKE, meta=FAKE, M=8, K=1024, Wq=FAKE, N=256, layout=0, w_scale=FAKE, w_zero=FAKE, w_sum=FAKE,
+             out_bias=None, Y=FAKE, ldy=256, acc=None)
+    a.update(kw)
+    rc = lib.basq_w4a4_gemm(a["Aq"], a["meta"], a["M"], a["K"], a["Wq"], a["N"], a["layout"], a["w_scale"],
+                            a["w_zero"], a["w_sum"], a["out_bias"], a["Y"], a["ldy"], a["acc"], None)
+    assert rc == code, B.basq_last_error()
+
+
+def test_fused_call_checks_workspace(lib):
+    need = B.basq_workspace_bytes(64, 1024, 256)
+    assert need >= 64 * 512 + 64 * 16 and need % 256 == 0
+    args = [FAKE, 64, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, FAKE, 256, 0, FAKE, FAKE, FAKE, None, FAKE, 256]
+    assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2000), need - 1, None) == B.BASQ_EWORKSPACE
+    assert "workspace too small" in B.basq_last_error()
+    assert lib.basq_linear_fused(*args, None, need, None) == B.BASQ_EINVAL
+    assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2010), need, None) == B.BASQ_EINVAL
+
+
+def test_zero_tokens_is_valid_without_a_launch(lib):
+    assert lib.basq_rotate_quant(None, 0, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, None, None, None, None) == 0
+    assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None) == 0
+
+
+def test_offline_helpers_reject_bad_arguments(lib):
+    assert lib.basq_quantize_weights(None, 8, 64, 64, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_quantize_weights(FAKE, 8, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_fused_bias(FAKE, 0, 64, FAKE, FAKE, None, None, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_calibrate_bias(FAKE, 16, 1024, 1024, 1024, None, FAKE, FAKE, 16 * 1024 * 4 - 1, None) == B.BASQ_EWORKSPACE
+    assert lib.basq_calibrate_bias(FAKE, 0, 1024, 1024, 1024, None, FAKE, FAKE, 1 << 20, None) == B.BASQ_EINVAL
+    assert lib.basq_hadamard28(None) == B.BASQ_EINVAL
+
+
+def test_hadamard28_table_matches_oracle(lib):
+    """The rotation for 28 * 2^t channels needs the same sign table on both sides; the library
+    builds its own from the Paley construction."""
+    np.testing.assert_array_equal(B.basq_hadamard28().numpy(), oracle.hadamard_paley28())

@@ -1,0 +1,189 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results (codes, row sums, INT32 accumulators) bit-exact; bf16 outputs within
+2e-2 of max|ref|; code flip rate vs the oracle's own rotation <= 1e-4 (see parity_util)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_15689_amd import binding as B
+from paper_2506_15689_amd import synth_inputs as si
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_case(lay, **kw):
+    rows = kw.pop("rows", None)
+    blas = kw.pop("use_blas_gemm", False)
+    case = pu.make_case(lay, **kw)
+    announce(f"M={case.M} K={case.K} N={case.N} rot={case.rot_size} clip=({case.clip_lo},{case.clip_hi})")
+    d = pu.to_device(case)
+    g = pu.run_gpu(case, d)
+    stats = pu.check_parity(case, g, rows=rows, use_blas_gemm=blas)
+    announce(f"ok {stats}")
+    return stats
+
+
+# ---------------------------------------------------------------- small and mid-size, element by element
+
+def test_c1_full():
+    run_case(si.make_layer(si.CONFIGS["C1"]))
+
+
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (33, 256, 40), (17, 4096, 96)])
+def test_ragged_multi_tile(M, K, N):
+    run_case(si.make_tiny(M, K, N, seed=M))
+
+
+@pytest.mark.parametrize("K,rot", [(1024, 128), (512, 64), (256, 32), (64, 2)])
+def test_blockwise_rotation(K, rot):
+    run_case(si.make_tiny(48, K, 64, seed=K + rot), rot_size=rot)
+
+
+@pytest.mark.parametrize("K", [28 * 64, 28 * 16, 2 * 28 * 32])
+def test_kronecker_rotation_with_h28(K):
+    rot = K if K != 2 * 28 * 32 else 28 * 32
+    run_case(si.make_tiny(70, K, 100, seed=K, act="swiglu", clip=0.85), rot_size=rot)
+
+
+def test_asymmetric_scale_and_unequal_clips_and_layer_bias():
+    cfg = si.LayerConfig("as", 0, 96, 1024, 160, 4, 20.0, 0.9, 0.02)
+    lay = si.make_layer(cfg, seed=77, with_layer_bias=True)
+    rng = np.random.default_rng(5)
+    sa = rng.uniform(0.7, 1.5, 1024).astype(np.float32)
+    run_case(lay, act_scale=sa, clip_lo=0.95, clip_hi=0.8)
+
+
+def test_no_bias_no_out_bias():
+    run_case(si.make_tiny(40, 512, 72, seed=9), use_bias=False, use_out_bias=False)
+
+
+@pytest.mark.parametrize("name", ["C3_M1", "C3_M4", "C3_M16"])
+def test_decode_shapes_full(name):
+    run_case(si.make_layer(si.CONFIGS[name]), use_blas_gemm=True)
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 24), (3, 512, 16), (16, 256, 100), (5, 96, 33)])
+def test_decode_ragged(M, K, N):
+    run_case(si.make_tiny(M, K, N, seed=3 * M + N), rot_size=K if K != 96 else 32)
+
+
+# ---------------------------------------------------------------- edge cases
+
+def test_zero_tokens_is_a_no_op():
+    dev = "cuda"
+    K, N = 256, 64
+    X = torch.empty((0, K), dtype=torch.bfloat16, device=dev)
+    Aq, meta = B.alloc_activation_buffers(0, K, dev)
+    B.basq_rotate_quant(X, K, None, None, 0.9, 0.9, Aq, meta)
+    Wq, ws, wz, wsum = B.alloc_weight_buffers(N, K, dev)
+    Y = torch.empty((0, N), dtype=torch.bfloat16, device=dev)
+    B.basq_w4a4_gemm(Aq, meta, Wq, ws, wz, wsum, None, Y)
+    torch.cuda.synchronize()
+
+
+def test_degenerate_tokens_match_oracle():
+    """Constant token, token with a NaN, token with +inf, all-zero token: same codes and records
+    as the oracle's quantiser given the GPU's rotation output."""
+    dev = "cuda"
+    K = 512
+    lay = si.make_tiny(8, K, 16, seed=21)
+    X = lay.X.clone().float()
+    X[1, :] = 0.0
+    X[2, :] = 0.0
+    X[2, 0] = 1.0                       # rotates to a constant token (every entry +1/sqrt(K))
+    X[3, 7] = float("nan")
+    X[4, 9] = float("inf")
+    X = X.to(torch.bfloat16)
+    Aq, meta = B.alloc_activation_buffers(8, K, dev)
+    rot = torch.empty((8, K), dtype=torch.float32, device=dev)
+    B.basq_rotate_quant(X.to(dev), K, None, None, 1.0, 1.0, Aq, meta, rot)
+    torch.cuda.synchronize()
+    r = rot.cpu().numpy()
+    assert np.all(r[1] == 0) and np.allclose(r[2], 1 / np.sqrt(K))
+    tq = oracle.quantize_tokens(r, None, None, 1.0, 1.0)
+    codes = oracle.unpack_codes(Aq.cpu().numpy())
+    mh = meta.cpu().numpy()
+    np.testing.assert_array_equal(codes, tq.codes)
+    np.testing.assert_array_equal(mh[:, 0].copy().view(np.uint32), tq.scale[:, 0].view(np.uint32))
+    np.testing.assert_array_equal(mh[:, 1].copy().view(np.uint32), tq.lo[:, 0].view(np.uint32))
+    np.testing.assert_array_equal(mh[:, 2], tq.rowsum[:, 0])
+    assert mh[1, 0].view(np.float32) == 1.0 and (codes[1] == 0).all()
+
+
+def test_strided_input_and_output():
+    dev = "cuda"
+    lay = si.make_tiny(50, 256, 48, seed=31)
+    case = pu.make_case(lay)
+    d = pu.to_device(case)
+    Xbig = torch.zeros((50, 256 + 64), dtype=torch.bfloat16, device=dev)
+    Xbig[:, :256] = d.X
+    Ybig = torch.zeros((50, 48 + 16), dtype=torch.bfloat16, device=dev)
+    Aq, meta = B.alloc_activation_buffers(50, 256, dev)
+    Aq2, meta2 = B.alloc_activation_buffers(50, 256, dev)
+    Y = torch.empty((50, 48), dtype=torch.bfloat16, device=dev)
+    B.basq_rotate_quant(Xbig[:, :256], 256, d.bias, None, 0.9, 0.9, Aq, meta)
+    B.basq_rotate_quant(d.X, 256, d.bias, None, 0.9, 0.9, Aq2, meta2)
+    B.basq_w4a4_gemm(Aq, meta, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Ybig[:, :48])
+    B.basq_w4a4_gemm(Aq2, meta2, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Y)
+    torch.cuda.synchronize()
+    assert torch.equal(Aq, Aq2) and torch.equal(meta[:, :3], meta2[:, :3])
+    assert torch.equal(Ybig[:, :48], Y)
+    assert (Ybig[:, 48:] == 0).all()
+
+
+def test_same_input_twice_gives_identical_bits():
+    lay = si.make_tiny(300, 1024, 200, seed=41)
+    case = pu.make_case(lay)
+    d = pu.to_device(case)
+    g1 = pu.run_gpu(case, d)
+    g2 = pu.run_gpu(case, d)
+    np.testing.assert_array_equal(g1.codes, g2.codes)
+    np.testing.assert_array_equal(g1.acc, g2.acc)
+    np.testing.assert_array_equal(g1.y_bits, g2.y_bits)
+    np.testing.assert_array_equal(g1.rot.view(np.uint32), g2.rot.view(np.uint32))
+
+
+# ---------------------------------------------------------------- offline helpers
+
+@pytest.mark.parametrize("N,K", [(64, 512), (100, 1792)])
+def test_weight_quantiser_and_fused_bias(N, K):
+    dev = "cuda"
+    lay = si.make_tiny(16, K, N, seed=N)
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    wq = oracle.quantize_weights(w)
+    Wq, ws, wz, wsum = B.alloc_weight_buffers(N, K, dev)
+    B.basq_quantize_weights(lay.W_rot.to(dev), Wq, ws, wz, wsum)
+    rng = np.random.default_rng(N)
+    bc = rng.standard_normal(K).astype(np.float32)
+    lb = rng.standard_normal(N).astype(np.float32)
+    ob = torch.empty(N, dtype=torch.float32, device=dev)
+    B.basq_fused_bias(Wq, ws, wz, torch.from_numpy(bc).to(dev), torch.from_numpy(lb).to(dev), ob)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(oracle.unpack_codes(Wq.cpu().numpy()), wq.codes)
+    np.testing.assert_array_equal(si.bf16_bits(ws.cpu()), wq.scale_bits)
+    np.testing.assert_array_equal(si.bf16_bits(wz.cpu()), wq.zero_bits)
+    np.testing.assert_array_equal(wsum.cpu().numpy().view(np.uint32), wq.wsum.view(np.uint32))
+    np.testing.assert_allclose(ob.cpu().numpy(), oracle.fused_bias(wq, bc, lb), rtol=1e-6, atol=1e-6)
+
+
+@pytest.mark.parametrize("K,rot", [(1024, 1024), (1792, 1792)])
+def test_bias_calibration(K, rot):
+    dev = "cuda"
+    lay = si.make_tiny(256, K, 8, seed=K)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    ref = oracle.channel_bias(x, rot)
+    out = torch.empty(K, dtype=torch.float32, device=dev)
+    ws = torch.empty(256 * K, dtype=torch.float32, device=dev)
+    B.basq_calibrate_bias(lay.X.to(dev), rot, None, out, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-5, atol=2e-6)
