@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 rotated linear layer on one MI355X.
+
+A step is one pass of the whole hot path -- online rotation + bias + per-token INT4 quantisation,
+then the INT4 x INT4 GEMM with fused de-quantisation -- over one batch of synthetic activations
+that already sit in HBM.  Prints ONE JSON line:
+
+  value        whole-layer throughput, 2*M*N*K integer operations per second of step time (TOPS)
+  roofline     the dominant kernel (the GEMM, int8 MFMA bound; for decode shapes HBM bound)
+  roofline_rotate_quant   the rotate+bias+quant kernel against HBM bandwidth
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload (context only)
+
+Kernel durations come from HIP events recorded on the launch stream around each of the two
+kernels inside the timed region.  Buffers rotate through several distinct sets so repeated steps
+do not find their inputs in the 256 MB last-level cache.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), bytes.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--config", default="C2", help="workload name from synth_inputs.CONFIGS")
+    p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
+    return p.parse_args()
+
+
+def algorithmic_bytes_rotate_quant(M, K):
+    # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes of token record out
+    return M * (2 * K + K // 2 + 16)
+
+
+def algorithmic_bytes_gemm(M, K, N):
+    # codes of both operands, token records, per-channel vectors, bf16 output
+    return M * (K // 2 + 16) + N * (K // 2) + N * (2 + 2 + 4 + 4) + 2 * M * N
+
+
+def cpu_baseline(cfg, lay, sample_tokens):
+    """Time the oracle (as it stands) on the first `sample_tokens` tokens x all N."""
+    import numpy as np
+    import oracle
+    from paper_2506_15689_amd import synth_inputs as si
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X[:sample_tokens]))
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    xc = oracle.bf16_to_f32(si.bf16_bits(lay.X_calib))
+    bc = oracle.channel_bias(xc, cfg.rot_size)            # offline parts are not timed
+    wq = oracle.quantize_weights(w)
+    c = oracle.fused_bias(wq, bc, None)
+    oracle.hadamard_matrix(cfg.rot_size)                  # the dense matrix is a constant: built once
+    t0 = time.perf_counter()
+    res = oracle.linear(x, cfg.rot_size, bc, None, cfg.clip, cfg.clip, wq, c)
+    dt = time.perf_counter() - t0
+    ops = 2.0 * sample_tokens * cfg.N * cfg.K
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {sample_tokens} of {lay.X.shape[0]} tokens x all N={cfg.N}, K={cfg.K}: "
+                      f"{dt:.2f} s for rotation (fp64 dense) + quantiser + int32 triple-loop GEMM + dequant",
+            "seconds": dt, "checksum": float(np.abs(res.y).sum())}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the layer shards over tokens or output channels without communication, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_15689_amd import binding as B
+    from paper_2506_15689_amd import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = si.CONFIGS[args.config]
+    M = args.M if args.M > 0 else cfg.M
+    K, N = cfg.K, cfg.N
+    lay = si.make_layer(cfg, M=M)
+
+    # ---- offline preparation, all through the library -------------------------------------
+    W = lay.W_rot.to(dev)
+    Wq, w_scale, w_zero, w_sum = B.alloc_weight_buffers(N, K, dev)
+    B.basq_quantize_weights(W, Wq, w_scale, w_zero, w_sum)
+    Xc = lay.X_calib.to(dev)
+    bias = torch.empty(K, dtype=torch.float32, device=dev)
+    cal_ws = torch.empty(Xc.shape[0] * K, dtype=torch.float32, device=dev)
+    B.basq_calibrate_bias(Xc, cfg.rot_size, None, bias, cal_ws)
+    out_bias = torch.empty(N, dtype=torch.float32, device=dev)
+    B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
+    torch.cuda.synchronize()
+    del W, cal_ws, Xc
+
+    # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
+    per_set = M * K * 2 + M * (K // 2) + M * 16 + M * N * 2
+    nsets = args.sets if args.sets > 0 else max(2, min(32, -(-(640 << 20) // per_set)))
+    X0 = lay.X.to(dev)
+    sets = []
+    for i in range(nsets):
+        Xi = X0 if i == 0 else torch.roll(X0, shifts=i, dims=0).contiguous()
+        Aq, meta = B.alloc_activation_buffers(M, K, dev)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        sets.append((Xi, Aq, meta, Y))
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        Xi, Aq, meta, Y = sets[i % nsets]
+        if ev is not None:
+            ev[0].record(stream)
+        B.basq_rotate_quant(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y, None, stream=stream)
+        if ev is not None:
+            ev[2].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    rq_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    ops = 2.0 * M * N * K
+    value = ops / (ms_step * 1e-3) / 1e12
+
+    rq_bytes = algorithmic_bytes_rotate_quant(M, K)
+    gemm_bytes = algorithmic_bytes_gemm(M, K, N)
+    rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
+    decode = M <= 16
+    if decode:
+        ach = gemm_bytes / (gemm_ms * 1e-3) / 1e9
+        roof = {"kernel": "gemv_w4a4_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
+                "algorithmic_bytes": gemm_bytes, "avg_kernel_ms": gemm_ms}
+    else:
+        ach = ops / (gemm_ms * 1e-3) / 1e12
+        roof = {"kernel": "gemm_w4a4_kernel", "bound": "mfma", "achieved": ach, "peak": INT8_PEAK_TOPS,
+                "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
+                "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
+    roof_rq = {"kernel": "rotate_quant", "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": rq_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "rotate_quant")),
+               "algorithmic_bytes": rq_bytes, "avg_kernel_ms": rq_ms}
+
+    out = {
+        "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 x int4 -> int32 (int8 MFMA); rotation and quantiser in f32; bf16 in/out",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": cfg.rot_size,
+                   "clip": cfg.clip, "buffer_sets": nsets},
+        "rotate_quant_GBps": rq_gbs,
+        "roofline": roof,
+        "roofline_rotate_quant": roof_rq,
+    }
+    if not args.no_cpu_baseline:
+        # about 2e11 integer operations keep the oracle busy for 10-30 s on the host cores
+        sample = max(1, min(M, int(round(2e11 / (2.0 * N * K)))))
+        out["cpu_baseline"] = cpu_baseline(cfg, lay, sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
