@@ -10,8 +10,8 @@ that already sit in HBM.  Prints ONE JSON line:
   roofline_rotate_quant   the rotate+bias+quant kernel against HBM bandwidth
   cpu_baseline the CPU oracle timed on a bounded sample of the same workload (context only)
 
-Kernel durations come from HIP events recorded on the launch stream around each of the two
-kernels inside the timed region.  Buffers rotate through several distinct sets so repeated steps
+Kernel durations come from HIP events recorded on the launch stream around K back-to-back
+launches of each kernel inside the timed region.  Buffers rotate through several distinct sets so repeated steps
 do not find their inputs in the 256 MB last-level cache.
 """
 from __future__ import annotations
@@ -42,6 +42,8 @@ def parse_args():
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
+    p.add_argument("--only", default="", choices=["", "rotate_quant"],
+                   help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
     return p.parse_args()
 
 
@@ -105,7 +107,7 @@ def main():
     W = lay.W_rot.to(dev)
     Wq, w_scale, w_zero, w_sum = B.alloc_weight_buffers(N, K, dev)
     B.basq_quantize_weights(W, Wq, w_scale, w_zero, w_sum)
-    Xc = lay.X_calib.to(dev)
+    Xc = lay.X_calib[:4096].to(dev)           # the bias is calibrated on at most 4096 tokens
     bias = torch.empty(K, dtype=torch.float32, device=dev)
     cal_ws = torch.empty(Xc.shape[0] * K, dtype=torch.float32, device=dev)
     B.basq_calibrate_bias(Xc, cfg.rot_size, None, bias, cal_ws)
@@ -115,53 +117,74 @@ def main():
     del W, cal_ws, Xc
 
     # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
-    per_set = M * K * 2 + M * (K // 2) + M * 16 + M * N * 2
+    rq_only = args.only == "rotate_quant"
+    per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2)
     nsets = args.sets if args.sets > 0 else max(2, min(32, -(-(640 << 20) // per_set)))
     X0 = lay.X.to(dev)
     sets = []
     for i in range(nsets):
         Xi = X0 if i == 0 else torch.roll(X0, shifts=i, dims=0).contiguous()
         Aq, meta = B.alloc_activation_buffers(M, K, dev)
-        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        Y = None if rq_only else torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         sets.append((Xi, Aq, meta, Y))
+    workspace = torch.empty(max(256, B.basq_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
 
-    def step(i, ev=None):
-        Xi, Aq, meta, Y = sets[i % nsets]
-        if ev is not None:
-            ev[0].record(stream)
+    def rotate_quant(i):
+        Xi, Aq, meta, _ = sets[i % nsets]
         B.basq_rotate_quant(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, stream=stream)
-        if ev is not None:
-            ev[1].record(stream)
+
+    def gemm(i):
+        _, Aq, meta, Y = sets[i % nsets]
         B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y, None, stream=stream)
-        if ev is not None:
-            ev[2].record(stream)
 
+    def step(i):
+        """One pass of the whole hot path: the single fused entry point."""
+        Xi, _, _, Y = sets[i % nsets]
+        B.basq_linear_fused(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Wq, w_scale, w_zero, w_sum, out_bias,
+                            Y, workspace, stream=stream)
+
+    def timed(fn, count):
+        """`count` back-to-back calls bracketed by two events on the launch stream; ms per call."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(count):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / count
+        return e0.elapsed_time(e1) / count, wall_ms
+
+    whole = rotate_quant if rq_only else step
+    for i in range(nsets):                      # every set holds valid codes before anything is timed
+        rotate_quant(i)
     for i in range(args.warmup):
-        step(i)
+        whole(i)
+        rotate_quant(i)
+        if not rq_only:
+            gemm(i)
     torch.cuda.synchronize()
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    ms_step = wall * 1e3 / args.steps
-    rq_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
-    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    ops = 2.0 * M * N * K
+    # the timed region: K steps of the whole path, then K launches of each kernel on its own so
+    # that each kernel's average duration is known (events around every single launch would add
+    # several microseconds of their own to kernels this short)
+    _, ms_step = timed(whole, args.steps)
+    rq_ms, _ = timed(rotate_quant, args.steps)
+    gemm_ms = float("nan") if rq_only else timed(gemm, args.steps)[0]
+    ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
     rq_bytes = algorithmic_bytes_rotate_quant(M, K)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     decode = M <= 16
-    if decode:
+    if rq_only:
+        roof = None
+    elif decode:
         ach = gemm_bytes / (gemm_ms * 1e-3) / 1e9
         roof = {"kernel": "gemv_w4a4_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
@@ -177,17 +200,17 @@ def main():
 
     out = {
         "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
-        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": rq_gbs if rq_only else value, "unit": "GB/s" if rq_only else "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 x int4 -> int32 (int8 MFMA); rotation and quantiser in f32; bf16 in/out",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": cfg.rot_size,
                    "clip": cfg.clip, "buffer_sets": nsets},
         "rotate_quant_GBps": rq_gbs,
-        "roofline": roof,
+        "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not rq_only:
         # about 2e11 integer operations keep the oracle busy for 10-30 s on the host cores
         sample = max(1, min(M, int(round(2e11 / (2.0 * N * K)))))
         out["cpu_baseline"] = cpu_baseline(cfg, lay, sample)

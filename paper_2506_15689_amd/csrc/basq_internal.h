@@ -30,6 +30,9 @@ struct RotateQuantArgs {
     float* rot_out;           // optional
 };
 int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s);
+// register-resident kernel for rot_size == K in {4096, 8192} (rotate_quant_pow2.hip)
+bool rotate_quant_pow2_applicable(const RotateQuantArgs& a);
+int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s);
 
 struct GemmArgs {
     const uint8_t* Aq;

@@ -1,0 +1,322 @@
+// Fast rotate + bias + quantise kernel for rot_size == K in {4096, 8192}: one wavefront per token,
+// the token never leaves registers except for one wave-private LDS transpose.
+// (Paper Sec. 5.2 applies the online Hadamard as matrix products on the matrix cores instead of a
+// pure butterfly recursion; here the first five stages are one bf16 MFMA -- exact, since the inputs
+// are bf16 and the matrix entries are +-2^-6 or +-1 -- and the remaining stages are fp32
+// butterflies in registers.)
+//
+// Channel index e (12 bits for K = 4096; bit 12 for K = 8192 rides along in registers).
+//   load      lane l reads 8 consecutive bf16 (16 B); 8 (16) loads of 1 KB each per token.
+//             e = 512*c + 8*chunk(l) + t,  chunk bits (e3..e8) <- lane bits (2,3,0,1,4,5)
+//   MFMA      D = A.B, A = the 16 x 32 slice of the token (row = l%16, k = 8*(l/16) + t), B = H_32
+//             over the index bits (e0,e1,e2,e7,e8), columns permuted so that output bit e0 lands
+//             in the half index h and (e1,e2,e7,e8) in output lane bits 0..3.
+//             After it a lane holds d[c][h][r]: e0 = h, (e5,e6) = r, (e9..) = c,
+//             lane bits (0,1,2,3,4,5) = (e1,e2,e7,e8,e3,e4).
+//   stages    e5, e6, e9, e10, e11 (, e12) in registers.
+//   transpose through LDS (16 KB per wave, 16-byte accesses, bank-conflict free) to the layout
+//             lane bits (0..5) = (e5..e10), registers = (e0..e4, e11 (, e12)).
+//   stages    e3, e4 in registers.
+//   now a lane owns 32 consecutive channels (x2 or x4): bias, min/max, quantise, pack, 16-byte stores.
+#include "basq_internal.h"
+
+namespace basq {
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+constexpr int P2_WAVES = 4;                 // wavefronts per workgroup
+constexpr int P2_THREADS = P2_WAVES * 64;
+constexpr int P2_LDS_WORDS = 4096;          // per wave
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141;
+constexpr int DPP_ROW_MIRROR = 0x140;
+
+__device__ __forceinline__ float wave_min_f(float v) {
+    v = fminf(v, dpp_f<DPP_QUAD_XOR1>(v));
+    v = fminf(v, dpp_f<DPP_QUAD_XOR2>(v));
+    v = fminf(v, dpp_f<DPP_ROW_HALF_MIRROR>(v));
+    v = fminf(v, dpp_f<DPP_ROW_MIRROR>(v));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fminf(fminf(r0, r1), fminf(r2, r3));
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+    v = fmaxf(v, dpp_f<DPP_QUAD_XOR1>(v));
+    v = fmaxf(v, dpp_f<DPP_QUAD_XOR2>(v));
+    v = fmaxf(v, dpp_f<DPP_ROW_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f<DPP_ROW_MIRROR>(v));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+    v += dpp_i<DPP_QUAD_XOR1>(v);
+    v += dpp_i<DPP_QUAD_XOR2>(v);
+    v += dpp_i<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_i<DPP_ROW_MIRROR>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+
+#define BFLY(x, y) do { const float _a = (x), _b = (y); (x) = _a + _b; (y) = _a - _b; } while (0)
+
+// NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
+// sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
+template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
+__global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
+    constexpr int K = 512 * NC;
+    constexpr int NH = NC / 8;                  // number of 4096-channel halves (bit 12)
+    constexpr bool PREFETCH = NC == 8;
+    static_assert(NC == 8 || NC == 16, "K must be 4096 or 8192");
+    __shared__ __attribute__((aligned(16))) float lds[P2_WAVES * P2_LDS_WORDS];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float* wl = lds + wave * P2_LDS_WORDS;
+
+    // ---- constants of this lane -------------------------------------------------------------
+    // B operand: column j' = lane%16 of half h, k = 8*(lane/16) + t; input index bits (t0,t1,t2,g0,g1),
+    // output index bits (h, j'0, j'1, j'2, j'3): sign = parity(popcount(kin & jout)).
+    v8bf bop[2];
+    {
+        const int jp = lane & 15, g = lane >> 4;
+        const uint16_t mag = FOLD_NORM ? (uint16_t)(((127 - (NC == 8 ? 6 : 0)) << 7)) : (uint16_t)0x3F80;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            v8s tmp;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int kin = t | (g << 3), jout = h | (jp << 1);
+                tmp[t] = (short)(mag | ((__builtin_popcount(kin & jout) & 1) ? 0x8000 : 0));
+            }
+            bop[h] = __builtin_bit_cast(v8bf, tmp);
+        }
+    }
+    // global load: chunk bits (e3,e4,e5,e6,e7,e8) <- lane bits (2,3,0,1,4,5)
+    const int chunk = ((lane >> 2) & 3) | ((lane & 3) << 2) | (lane & 0x30);
+    // LDS write base (words): see the address map in the file header
+    //   [3:2] = (e1^e5, e2^e6), [5:4] = (e7,e8), [7:6] = (e5,e6), [9:8] = (e3,e4), [11:10] = (e9,e10), [1:0] = (e0,e11)
+    const int wbase = ((lane & 3) << 2) | (((lane >> 2) & 3) << 4) | (((lane >> 4) & 3) << 8);
+    // LDS read base: lane bits (0..5) = (e5..e10)
+    const int rbase = ((lane & 3) << 2) | (((lane >> 2) & 3) << 4) | ((lane & 3) << 6) | (((lane >> 4) & 3) << 10);
+
+    const int wave_id = blockIdx.x * P2_WAVES + wave;
+    const int wave_stride = gridDim.x * P2_WAVES;
+
+    uint4 raw[NC];
+    auto load_token = [&](int64_t m) {
+        const uint16_t* x = a.X + m * a.ldx + 8 * chunk;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) raw[c] = *reinterpret_cast<const uint4*>(x + 512 * c);
+    };
+
+    int64_t m = wave_id;
+    if (PREFETCH && m < a.M) load_token(m);
+    for (; m < a.M; m += wave_stride) {
+        if (!PREFETCH) load_token(m);
+        // ---- first five stages on the matrix core ---------------------------------------------
+        float d[NC][2][4];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const v8bf aop = __builtin_bit_cast(v8bf, raw[c]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                v4f acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[h], acc, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) d[c][h][r] = acc[r];
+            }
+        }
+        // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
+        const int64_t mnext = m + wave_stride;
+        if (PREFETCH && mnext < a.M) load_token(mnext);
+
+        // ---- stages e5, e6 (r bits) and e9.. (c bits) --------------------------------------------
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                BFLY(d[c][h][0], d[c][h][1]);
+                BFLY(d[c][h][2], d[c][h][3]);
+                BFLY(d[c][h][0], d[c][h][2]);
+                BFLY(d[c][h][1], d[c][h][3]);
+            }
+#pragma unroll
+        for (int s = 1; s < NC; s <<= 1)
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if ((c & s) == 0)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) BFLY(d[c][h][r], d[c + s][h][r]);
+
+        // ---- transpose through LDS, one 4096-channel half at a time --------------------------------
+        // p[half][e11][idx], idx = e0..e4
+        float p[NH][2][32];
+#pragma unroll
+        for (int hf = 0; hf < NH; ++hf) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c01 = 0; c01 < 4; ++c01) {
+                    const int r0 = r & 1, r1 = r >> 1;
+                    // [3:2] ^= (r0, r1); [7:6] = (r0, r1); [11:10] = c01
+                    const int addr = (wbase ^ ((r0 << 2) | (r1 << 3))) | (r0 << 6) | (r1 << 7) | (c01 << 10);
+                    v4f v;
+                    v[0] = d[8 * hf + c01][0][r];          // (e0 = 0, e11 = 0)
+                    v[1] = d[8 * hf + c01][1][r];          // (1, 0)
+                    v[2] = d[8 * hf + c01 + 4][0][r];      // (0, 1)
+                    v[3] = d[8 * hf + c01 + 4][1][r];      // (1, 1)
+                    *reinterpret_cast<v4f*>(wl + addr) = v;
+                }
+            // LDS serves one wave's instructions in issue order, so the reads below see these writes
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int e1 = q & 1, e2 = (q >> 1) & 1, e3 = (q >> 2) & 1, e4 = q >> 3;
+                const int addr = (rbase ^ ((e1 << 2) | (e2 << 3))) | (e3 << 8) | (e4 << 9);
+                const v4f v = *reinterpret_cast<const v4f*>(wl + addr);
+                const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
+                p[hf][0][idx] = v[0];
+                p[hf][0][idx | 1] = v[1];
+                p[hf][1][idx] = v[2];
+                p[hf][1][idx | 1] = v[3];
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- stages e3, e4 ----------------------------------------------------------------------
+#pragma unroll
+        for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) if ((i & 8) == 0) BFLY(p[hf][b][i], p[hf][b][i | 8]);
+#pragma unroll
+                for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[hf][b][i], p[hf][b][i | 16]);
+            }
+        // ---- normalise, bias, min/max ---------------------------------------------------------------
+        // this lane owns channels e = 4096*hf + 2048*b + 32*lane + i
+        float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+        for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int e0 = 4096 * hf + 2048 * b + 32 * lane;
+#pragma unroll
+                for (int i4 = 0; i4 < 8; ++i4) {
+                    float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
+                    if (HAS_BIAS) bb = *reinterpret_cast<const float4*>(a.bias + e0 + 4 * i4);
+                    if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(a.act_scale + e0 + 4 * i4);
+                    const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+                    const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
+                    float rr[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float r = p[hf][b][4 * i4 + j];
+                        if (!FOLD_NORM) r = r * norm;
+                        rr[j] = r;
+                        const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
+                        p[hf][b][4 * i4 + j] = v;
+                        mn = fminf(mn, v);
+                        mx = fmaxf(mx, v);
+                    }
+                    if (ROT_OUT)
+                        *reinterpret_cast<float4*>(a.rot_out + m * (int64_t)K + e0 + 4 * i4) =
+                            make_float4(rr[0], rr[1], rr[2], rr[3]);
+                }
+            }
+        mn = wave_min_f(mn);
+        mx = wave_max_f(mx);
+
+        const float lo = a.clip_lo * mn;
+        const float hi = a.clip_hi * mx;
+        float s = __fdiv_rn(hi - lo, 15.0f);
+        if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
+        const float inv = __fdiv_rn(1.0f, s);
+        const float nlo = -(lo * inv);
+
+        // ---- quantise, pack, store -----------------------------------------------------------------
+        int sum = 0;
+#pragma unroll
+        for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                uint32_t words[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    uint32_t ev = 0, od = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j], inv, nlo), 0.0f, 15.0f);
+                        const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
+                        ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
+                        od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
+                    }
+                    sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
+                    sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
+                    words[w] = ev | (od << 4);
+                }
+                uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
+                *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
+            }
+        sum = wave_sum_i(sum);
+        if (lane == 0) {
+            basq_tokmeta mt;
+            mt.scale = s; mt.lo = lo; mt.rowsum = sum; mt.reserved = 0;
+            a.meta[m] = mt;
+        }
+    }
+}
+
+template <int NC, bool FOLD, bool HB, bool HS>
+int launch_flags(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm) {
+    if (a.rot_out)
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+    else
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+    return check_hip(hipGetLastError(), "rotate_quant (pow2) launch");
+}
+
+template <int NC, bool FOLD>
+int launch_nc(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm) {
+    const bool hb = a.bias != nullptr, hs = a.act_scale != nullptr;
+    if (hb && hs) return launch_flags<NC, FOLD, true, true>(a, s, blocks, norm);
+    if (hb) return launch_flags<NC, FOLD, true, false>(a, s, blocks, norm);
+    if (hs) return launch_flags<NC, FOLD, false, true>(a, s, blocks, norm);
+    return launch_flags<NC, FOLD, false, false>(a, s, blocks, norm);
+}
+
+}  // namespace
+
+bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
+    return !a.has28 && a.rot_size == a.K && (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
+}
+
+int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {
+    const int64_t want = (a.M + P2_WAVES - 1) / P2_WAVES;
+    const unsigned blocks = (unsigned)(want < 512 ? want : 512);     // 2 workgroups per CU, waves loop over tokens
+    const float norm = (float)(1.0 / sqrt((double)a.K));
+    if (a.K == 4096) return launch_nc<8, true>(a, s, blocks, norm);
+    return launch_nc<16, false>(a, s, blocks, norm);
+}
+
+}  // namespace basq
