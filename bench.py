@@ -42,6 +42,7 @@ def parse_args():
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
+    p.add_argument("--no-bias", action="store_true", help="run the kernels without the channel bias (experiments)")
     p.add_argument("--only", default="", choices=["", "rotate_quant"],
                    help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
     return p.parse_args()
@@ -115,6 +116,8 @@ def main():
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
     torch.cuda.synchronize()
     del W, cal_ws, Xc
+    if args.no_bias:
+        bias = None
 
     # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
     rq_only = args.only == "rotate_quant"

@@ -38,19 +38,29 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_lib(verbose: bool = True) -> str:
-    """Compile every translation unit and link libbasq.so.  Always recompiles."""
+def build_lib(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
+    """Compile every translation unit and link libbasq.so.  Always recompiles.
+    `extra_flags` (e.g. -D tuning macros) and `out` exist for tuning experiments."""
+    global BUILD
+    if out != LIB:
+        BUILD = os.path.join(PKG, "_build", os.path.basename(out))
     os.makedirs(BUILD, exist_ok=True)
+    HIPCC_FLAGS.extend(extra_flags)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
         raise RuntimeError("link failed:\n" + proc.stdout)
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {out}")
+    return out
 
 
 if __name__ == "__main__":
-    build_lib()
+    # python -m paper_2506_15689_amd.build [--out path.so] [extra hipcc flags ...]
+    argv = sys.argv[1:]
+    out_path = LIB
+    if len(argv) >= 2 and argv[0] == "--out":
+        out_path, argv = os.path.abspath(argv[1]), argv[2:]
+    build_lib(extra_flags=argv, out=out_path)

@@ -14,7 +14,7 @@
 //             After it a lane holds d[c][h][r]: e0 = h, (e5,e6) = r, (e9..) = c,
 //             lane bits (0,1,2,3,4,5) = (e1,e2,e7,e8,e3,e4).
 //   stages    e5, e6, e9, e10, e11 (, e12) in registers.
-//   transpose through LDS (16 KB per wave, 16-byte accesses, bank-conflict free) to the layout
+//   transpose through LDS (8 KB per wave, reused per 2048 channels, 8-byte accesses, no bank conflicts) to the layout
 //             lane bits (0..5) = (e5..e10), registers = (e0..e4, e11 (, e12)).
 //   stages    e3, e4 in registers.
 //   now a lane owns 32 consecutive channels (x2 or x4): bias, min/max, quantise, pack, 16-byte stores.
@@ -30,7 +30,13 @@ typedef short v8s __attribute__((ext_vector_type(8)));
 
 constexpr int P2_WAVES = 4;                 // wavefronts per workgroup
 constexpr int P2_THREADS = P2_WAVES * 64;
-constexpr int P2_LDS_WORDS = 4096;          // per wave
+#ifndef P2_OCC_4096
+#define P2_OCC_4096 3
+#endif
+#ifndef P2_PREFETCH
+#define P2_PREFETCH 1
+#endif
+constexpr int P2_LDS_WORDS = 2048;          // per wave
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
@@ -81,15 +87,27 @@ __device__ __forceinline__ int wave_sum_i(int v) {
 // NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
 // sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
 template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
-__global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
+__global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
     constexpr int K = 512 * NC;
     constexpr int NH = NC / 8;                  // number of 4096-channel halves (bit 12)
-    constexpr bool PREFETCH = NC == 8;
+    constexpr bool PREFETCH = (NC == 8) && P2_PREFETCH;
     static_assert(NC == 8 || NC == 16, "K must be 4096 or 8192");
-    __shared__ __attribute__((aligned(16))) float lds[P2_WAVES * P2_LDS_WORDS];
+    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves) laid out so
+    // that lane l's i-th 16-byte piece sits at float4 index (piece group)*64 + l: conflict-free reads
+    constexpr int BIAS_WORDS = HAS_BIAS ? K : 0;
+    __shared__ __attribute__((aligned(16))) float lds[P2_WAVES * P2_LDS_WORDS + BIAS_WORDS];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* wl = lds + wave * P2_LDS_WORDS;
+    const float4* lbias = reinterpret_cast<const float4*>(lds + P2_WAVES * P2_LDS_WORDS);
+    if (HAS_BIAS) {
+        float4* dst = reinterpret_cast<float4*>(lds + P2_WAVES * P2_LDS_WORDS);
+        for (int f = threadIdx.x; f < K / 4; f += P2_THREADS) {
+            const int e = 4 * f;                          // channels e .. e+3 belong to lane (e%2048)/32, piece (e%32)/4
+            dst[((e >> 11) * 8 + ((e & 31) >> 2)) * 64 + ((e & 2047) >> 5)] = *reinterpret_cast<const float4*>(a.bias + e);
+        }
+        __syncthreads();
+    }
 
     // ---- constants of this lane -------------------------------------------------------------
     // B operand: column j' = lane%16 of half h, k = 8*(lane/16) + t; input index bits (t0,t1,t2,g0,g1),
@@ -110,12 +128,15 @@ __global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(Rotate
         }
     }
     // global load: chunk bits (e3,e4,e5,e6,e7,e8) <- lane bits (2,3,0,1,4,5)
+#ifdef P2_EXP_LINEAR_CHUNK
+    const int chunk = lane;
+#else
     const int chunk = ((lane >> 2) & 3) | ((lane & 3) << 2) | (lane & 0x30);
-    // LDS write base (words): see the address map in the file header
-    //   [3:2] = (e1^e5, e2^e6), [5:4] = (e7,e8), [7:6] = (e5,e6), [9:8] = (e3,e4), [11:10] = (e9,e10), [1:0] = (e0,e11)
-    const int wbase = ((lane & 3) << 2) | (((lane >> 2) & 3) << 4) | (((lane >> 4) & 3) << 8);
+#endif
+    // LDS write base (words), lane bits (0..5) = (e1,e2,e7,e8,e3,e4); address map at the transpose below
+    const int wbase = ((lane & 15) << 1) | (((lane >> 4) & 3) << 7);
     // LDS read base: lane bits (0..5) = (e5..e10)
-    const int rbase = ((lane & 3) << 2) | (((lane >> 2) & 3) << 4) | ((lane & 3) << 6) | (((lane >> 4) & 3) << 10);
+    const int rbase = ((lane & 15) << 1) | ((lane & 3) << 5) | (((lane >> 4) & 3) << 9);
 
     const int wave_id = blockIdx.x * P2_WAVES + wave;
     const int wave_stride = gridDim.x * P2_WAVES;
@@ -168,40 +189,44 @@ __global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(Rotate
 #pragma unroll
                         for (int r = 0; r < 4; ++r) BFLY(d[c][h][r], d[c + s][h][r]);
 
-        // ---- transpose through LDS, one 4096-channel half at a time --------------------------------
+        // ---- transpose through LDS, 2048 channels (one value of e11, e12) at a time ---------------------
+        // word address bits: [0] = e0, [2:1] = (e1^e5, e2^e6), [4:3] = (e7,e8), [6:5] = (e5,e6),
+        //                    [8:7] = (e3,e4), [10:9] = (e9,e10)
         // p[half][e11][idx], idx = e0..e4
         float p[NH][2][32];
 #pragma unroll
-        for (int hf = 0; hf < NH; ++hf) {
+        for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int c2 = 0; c2 < 2; ++c2) {
 #pragma unroll
-                for (int c01 = 0; c01 < 4; ++c01) {
-                    const int r0 = r & 1, r1 = r >> 1;
-                    // [3:2] ^= (r0, r1); [7:6] = (r0, r1); [11:10] = c01
-                    const int addr = (wbase ^ ((r0 << 2) | (r1 << 3))) | (r0 << 6) | (r1 << 7) | (c01 << 10);
-                    v4f v;
-                    v[0] = d[8 * hf + c01][0][r];          // (e0 = 0, e11 = 0)
-                    v[1] = d[8 * hf + c01][1][r];          // (1, 0)
-                    v[2] = d[8 * hf + c01 + 4][0][r];      // (0, 1)
-                    v[3] = d[8 * hf + c01 + 4][1][r];      // (1, 1)
-                    *reinterpret_cast<v4f*>(wl + addr) = v;
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int c01 = 0; c01 < 4; ++c01) {
+                        const int r0 = r & 1, r1 = r >> 1;
+                        const int addr = (wbase ^ ((r0 << 1) | (r1 << 2))) | (r0 << 5) | (r1 << 6) | (c01 << 9);
+                        const int c = 8 * hf + 4 * c2 + c01;
+#ifndef P2_EXP_NOLDS
+                        *reinterpret_cast<float2*>(wl + addr) = make_float2(d[c][0][r], d[c][1][r]);
+#endif
+                    }
+                // LDS serves one wave's instructions in issue order: the reads below see these writes,
+                // and the next round's writes do not overtake these reads
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int e1 = q & 1, e2 = (q >> 1) & 1, e3 = (q >> 2) & 1, e4 = q >> 3;
+                    const int addr = (rbase ^ ((e1 << 1) | (e2 << 2))) | (e3 << 7) | (e4 << 8);
+#ifndef P2_EXP_NOLDS
+                    const float2 v = *reinterpret_cast<const float2*>(wl + addr);
+#else
+                    const float2 v = make_float2(d[8 * hf + 4 * c2 + (q & 3)][0][q >> 2], d[8 * hf + 4 * c2 + (q & 3)][1][q >> 2]);
+#endif
+                    const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
+                    p[hf][c2][idx] = v.x;
+                    p[hf][c2][idx | 1] = v.y;
                 }
-            // LDS serves one wave's instructions in issue order, so the reads below see these writes
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int e1 = q & 1, e2 = (q >> 1) & 1, e3 = (q >> 2) & 1, e4 = q >> 3;
-                const int addr = (rbase ^ ((e1 << 2) | (e2 << 3))) | (e3 << 8) | (e4 << 9);
-                const v4f v = *reinterpret_cast<const v4f*>(wl + addr);
-                const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
-                p[hf][0][idx] = v[0];
-                p[hf][0][idx | 1] = v[1];
-                p[hf][1][idx] = v[2];
-                p[hf][1][idx | 1] = v[3];
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
-        }
 
         // ---- stages e3, e4 ----------------------------------------------------------------------
 #pragma unroll
@@ -224,7 +249,7 @@ __global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(Rotate
 #pragma unroll
                 for (int i4 = 0; i4 < 8; ++i4) {
                     float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
-                    if (HAS_BIAS) bb = *reinterpret_cast<const float4*>(a.bias + e0 + 4 * i4);
+                    if (HAS_BIAS) bb = lbias[((2 * hf + b) * 8 + i4) * 64 + lane];
                     if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(a.act_scale + e0 + 4 * i4);
                     const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
                     const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
@@ -256,6 +281,7 @@ __global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(Rotate
 
         // ---- quantise, pack, store -----------------------------------------------------------------
         int sum = 0;
+#ifndef P2_EXP_NOQUANT
 #pragma unroll
         for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
@@ -278,6 +304,7 @@ __global__ __launch_bounds__(P2_THREADS, 2) void rotate_quant_pow2_kernel(Rotate
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
             }
+#endif
         sum = wave_sum_i(sum);
         if (lane == 0) {
             basq_tokmeta mt;
@@ -313,7 +340,8 @@ bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {
     const int64_t want = (a.M + P2_WAVES - 1) / P2_WAVES;
-    const unsigned blocks = (unsigned)(want < 512 ? want : 512);     // 2 workgroups per CU, waves loop over tokens
+    const int64_t resident = 256 * (a.K == 4096 ? P2_OCC_4096 : 2);  // workgroups the chip holds at once
+    const unsigned blocks = (unsigned)(want < resident ? want : resident);   // waves loop over tokens
     const float norm = (float)(1.0 / sqrt((double)a.K));
     if (a.K == 4096) return launch_nc<8, true>(a, s, blocks, norm);
     return launch_nc<16, false>(a, s, blocks, norm);
