@@ -50,6 +50,9 @@ struct GemmArgs {
     int32_t* acc_out;
 };
 int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
+// direct-to-LDS kernel for K % 256 == 0 (gemm_w4a4_direct.hip)
+bool gemm_direct_applicable(const GemmArgs& a);
+int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
 
 int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq,

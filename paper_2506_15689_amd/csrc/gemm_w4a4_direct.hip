@@ -1,0 +1,257 @@
+// Prefill INT4 x INT4 -> INT32 GEMM, main kernel: operands go HBM/L2 -> LDS with direct-to-LDS
+// loads (no register staging), a ring of LDS stages, XOR-swizzled rows instead of padding, wave
+// tiles of 128 x 64 so that LDS traffic per MFMA stays low, and the de-quantisation fused into
+// the epilogue (paper Sec. 5.2; Fig. 6; Eq. 14).  Same arithmetic and nibble split as
+// gemm_w4a4.hip, which remains the fallback for K % 128 != 0.
+#include "basq_internal.h"
+
+namespace basq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int NUM_XCD = 8;
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// Wait until at most N of this wave's vector-memory operations (the direct-to-LDS loads) are still
+// outstanding, then join the workgroup barrier.  Written as one asm block: the compiler's own
+// barrier would first wait for ALL outstanding loads, which would serialise the LDS ring.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// BKB: packed bytes of K per row per stage (64 -> 128 codes).  STAGES: LDS ring depth.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, int STAGES, int MINOCC>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_direct_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+    constexpr int WAVES = WAVES_M * WAVES_N;
+    constexpr int THREADS = WAVES * 64;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int NCH = BKB / 16;                             // 16-byte chunks per row per stage
+    constexpr int ROWS = BM + BN;
+    constexpr int STAGE_BYTES = ROWS * BKB;
+    constexpr int LOADS = ROWS * NCH / THREADS;               // direct loads per thread per stage
+    static_assert((ROWS * NCH) % THREADS == 0, "stage does not divide over the threads");
+    static_assert(BKB == 64 || BKB == 128, "BKB");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[STAGES * STAGE_BYTES];
+
+    // ---- tile assignment (XCD-aware: ids congruent mod 8 run on one XCD and walk a compact band)
+    int tile_m, tile_n;
+    {
+        const int total = tiles_m * tiles_n;
+        const int pid = blockIdx.x;
+        int t = pid;
+        const int per_xcd = total / NUM_XCD;
+        if (pid < per_xcd * NUM_XCD) t = (pid % NUM_XCD) * per_xcd + pid / NUM_XCD;
+        constexpr int GROUP_M = 4;
+        const int band = t / (GROUP_M * tiles_n);
+        const int first_m = band * GROUP_M;
+        const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+        const int in_band = t - band * GROUP_M * tiles_n;
+        tile_m = first_m + in_band % rows;
+        tile_n = in_band / rows;
+    }
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+    const int KB = a.K / 2;
+    const int ksteps = KB / BKB;                              // K % (2*BKB) == 0 is checked by the launcher
+
+    // ---- direct loads: load i of wave w fills LDS chunks [(i*WAVES + w)*64, +64) of a stage; the lane
+    // picks the global chunk whose swizzled position is its LDS slot.  Rows past the matrix are clamped.
+    const uint8_t* gsrc[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int L = (i * WAVES + wave) * 64 + lane;
+        const int row = L / NCH, cpos = L % NCH;
+        const int swz = (BKB == 128) ? (row & 7) : ((row >> 1) & 3);
+        const int c = cpos ^ swz;
+        if (row < BM) {
+            int64_t m = m0 + row;
+            m = m < a.M ? m : a.M - 1;
+            gsrc[i] = a.Aq + m * KB + c * 16;
+        } else {
+            int n = n0 + row - BM;
+            n = n < a.N ? n : a.N - 1;
+            gsrc[i] = a.Wq + (int64_t)n * KB + c * 16;
+        }
+    }
+    auto issue_loads = [&](int ks) {
+        uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES;
+        const int koff = ks * BKB;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            __builtin_amdgcn_global_load_lds(GLB_PTR(gsrc[i] + koff), LDS_PTR(stage + (i * WAVES + wave) * 1024), 16, 0, 0);
+    };
+
+    // ---- fragment addressing: lane (frow, fhalf) reads chunk fhalf + 2h of its row, swizzled
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fswz = (BKB == 128) ? (frow & 7) : ((frow >> 1) & 3);
+    int foff[NCH / 2];
+#pragma unroll
+    for (int h = 0; h < NCH / 2; ++h) foff[h] = (((fhalf + 2 * h) ^ fswz) << 4);
+    const int a_row = (wm * WM + frow) * BKB;
+    const int b_row = (BM + wn * WN + frow) * BKB;
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // ---- prologue: fill STAGES-1 stages
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < ksteps) issue_loads(s);
+    if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS>(); else wait_loads_and_barrier<0>();
+
+    // packed fragments of the next (step, h): read from LDS one h ahead of the MFMAs that use them
+    v4i pa[TM], pb[TN];
+    auto read_frags = [&](const uint8_t* st, int h) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) pa[i] = *reinterpret_cast<const v4i*>(st + a_row + i * 32 * BKB + foff[h]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) pb[j] = *reinterpret_cast<const v4i*>(st + b_row + j * 32 * BKB + foff[h]);
+    };
+    read_frags(lds, 0);
+
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
+        // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
+#ifndef GD_EXP_NOLOADS
+        if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
+#endif
+
+#pragma unroll
+        for (int h = 0; h < NCH / 2; ++h) {
+            v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                alo[i] = pa[i] & 0x0F0F0F0F;
+                ahi[i] = (pa[i] >> 4) & 0x0F0F0F0F;
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                blo[j] = pb[j] & 0x0F0F0F0F;
+                bhi[j] = (pb[j] >> 4) & 0x0F0F0F0F;
+            }
+            if (h + 1 < NCH / 2) {
+                read_frags(st, h + 1);
+            } else {
+                // last h of the step: every read of this stage has been issued and consumed; pass the
+                // barrier (next stage complete and visible), start the next step's first reads, and
+                // only then run this h's MFMAs so that the LDS latency hides behind them
+                if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS>(); else wait_loads_and_barrier<0>();
+                if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], acc[i][j], 0, 0, 0);
+                }
+        }
+    }
+    __syncthreads();
+
+    // ---- epilogue: row and column constants through LDS (free now), then one bf16 per lane per store
+    float4* lrow_par = reinterpret_cast<float4*>(lds);
+    float4* lcol_par = lrow_par + BM;
+    for (int i = tid; i < BM; i += THREADS) {
+        int64_t m = m0 + i;
+        m = m < a.M ? m : a.M - 1;
+        const basq_tokmeta mt = a.meta[m];
+        lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, 0.0f);
+    }
+    for (int i = tid; i < BN; i += THREADS) {
+        int n = n0 + i;
+        n = n < a.N ? n : a.N - 1;
+        lcol_par[i] = make_float4(bf16_to_f32(a.w_scale[n]), bf16_to_f32(a.w_zero[n]), a.w_sum[n],
+                                  a.out_bias ? a.out_bias[n] : 0.0f);
+    }
+    __syncthreads();
+
+    const int col_in_tile = lane & 31, rgrp = lane >> 5;
+    float4 cp[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = wm * WM + i * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
+            const int64_t m = m0 + row;
+            if (m >= a.M) continue;
+            const float4 rp = lrow_par[row];
+            uint16_t* yrow = a.Y + m * a.ldy;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * WN + j * 32 + col_in_tile;
+#ifdef GD_EXP_NOEPI
+                if (n < a.N && acc[i][j][r] == 0x7fffffff) {
+#else
+                if (n < a.N) {
+#endif
+                    const int av = acc[i][j][r];
+                    const float t = (float)av - cp[j].y * rp.z;
+                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
+                    yrow[n] = f32_to_bf16(y);
+                    if (a.acc_out) a.acc_out[m * (int64_t)a.N + n] = av;
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, int STAGES, int MINOCC>
+int launch_direct(const GemmArgs& a, hipStream_t s) {
+    const int64_t tm = (a.M + BM - 1) / BM;
+    const int64_t tn = ((int64_t)a.N + BN - 1) / BN;
+    if (tm * tn > 0x7FFFFFFFll) return fail(BASQ_EINVAL, "w4a4_gemm: problem too large for one launch");
+    hipLaunchKernelGGL((gemm_w4a4_direct_kernel<BM, BN, WAVES_M, WAVES_N, BKB, STAGES, MINOCC>), dim3((unsigned)(tm * tn)),
+                       dim3(WAVES_M * WAVES_N * 64), 0, s, a, (int)tm, (int)tn);
+    return check_hip(hipGetLastError(), "w4a4_gemm (direct) launch");
+}
+
+}  // namespace
+
+bool gemm_direct_applicable(const GemmArgs& a) { return a.K % 256 == 0 && a.M >= 1; }
+
+namespace {
+// share of the launched tile slots that hold a real tile when `tiles` tiles run `slots` at a time
+double round_efficiency(int64_t tiles, int64_t slots) {
+    const int64_t rounds = (tiles + slots - 1) / slots;
+    return (double)tiles / (double)(rounds * slots);
+}
+}  // namespace
+
+int launch_gemm_direct(const GemmArgs& a, hipStream_t s) {
+#ifdef GEMM_DIRECT_CFG
+    return launch_direct<GEMM_DIRECT_CFG>(a, s);
+#else
+    // Three tilings; larger tiles reuse operands better (less L2 traffic per MFMA) but quantise
+    // worse on small problems.  256 CUs; the 4-wave tilings run two workgroups per CU.
+    auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * (((int64_t)a.N + bn - 1) / bn); };
+    const double s_big = 1.00 * round_efficiency(tiles(256, 256), 256);
+    const double s_mid = 0.95 * round_efficiency(tiles(256, 128), 512);
+    const double s_small = 0.85 * round_efficiency(tiles(128, 128), 512);
+    if (s_big >= s_mid && s_big >= s_small) return launch_direct<256, 256, 2, 4, 128, 2, 2>(a, s);
+    if (s_mid >= s_small) return launch_direct<256, 128, 2, 2, 64, 3, 2>(a, s);
+    return launch_direct<128, 128, 2, 2, 64, 3, 2>(a, s);
+#endif
+}
+
+}  // namespace basq
