@@ -29,8 +29,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 
-# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), bytes.
-MEASURED_TRAFFIC = {}
+# HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
+# under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
+MEASURED_TRAFFIC = {
+    ("C2", "rotate_quant"): 21264589, ("C2", "gemm"): 171217715,
+    ("C5", "rotate_quant"): 84447437, ("C5", "gemm"): 943563981,
+}
 
 
 def parse_args():
@@ -42,6 +46,8 @@ def parse_args():
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run a plain 256 MiB device copy three times (scales the HBM byte counters of a profiler run)")
     p.add_argument("--no-bias", action="store_true", help="run the kernels without the channel bias (experiments)")
     p.add_argument("--only", default="", choices=["", "rotate_quant"],
                    help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
@@ -181,6 +187,16 @@ def main():
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
+    if args.M > 0 or args.no_bias:
+        MEASURED_TRAFFIC.clear()                  # the stored counters belong to the unmodified configurations
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     rq_bytes = algorithmic_bytes_rotate_quant(M, K)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
@@ -194,7 +210,7 @@ def main():
                 "algorithmic_bytes": gemm_bytes, "avg_kernel_ms": gemm_ms}
     else:
         ach = ops / (gemm_ms * 1e-3) / 1e12
-        roof = {"kernel": "gemm_w4a4_kernel", "bound": "mfma", "achieved": ach, "peak": INT8_PEAK_TOPS,
+        roof = {"kernel": "gemm_w4a4_direct_kernel", "bound": "mfma", "achieved": ach, "peak": INT8_PEAK_TOPS,
                 "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
                 "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
     roof_rq = {"kernel": "rotate_quant", "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
