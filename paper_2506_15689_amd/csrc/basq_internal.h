@@ -33,6 +33,9 @@ int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s);
 // register-resident kernel for rot_size == K in {4096, 8192} (rotate_quant_pow2.hip)
 bool rotate_quant_pow2_applicable(const RotateQuantArgs& a);
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s);
+// kernel for rot_size == K == 14336 = 28 * 512 (rotate_quant_k28.hip)
+bool rotate_quant_k28_applicable(const RotateQuantArgs& a);
+int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s);
 
 struct GemmArgs {
     const uint8_t* Aq;

@@ -22,7 +22,11 @@ constexpr int NUM_XCD = 8;
 // barrier would first wait for ALL outstanding loads, which would serialise the LDS ring.
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
+#ifdef GD_EXP_NOBARRIER
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#else
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+#endif
 }
 
 // BKB: packed bytes of K per row per stage (64 -> 128 codes).  STAGES: LDS ring depth.
@@ -50,7 +54,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
         int t = pid;
         const int per_xcd = total / NUM_XCD;
         if (pid < per_xcd * NUM_XCD) t = (pid % NUM_XCD) * per_xcd + pid / NUM_XCD;
-        constexpr int GROUP_M = 4;
+#ifndef GD_GROUP_M
+#define GD_GROUP_M 4
+#endif
+        constexpr int GROUP_M = GD_GROUP_M;
         const int band = t / (GROUP_M * tiles_n);
         const int first_m = band * GROUP_M;
         const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
@@ -117,15 +124,53 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
         if (s < ksteps) issue_loads(s);
     if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS>(); else wait_loads_and_barrier<0>();
 
-    // packed fragments of the next (step, h): read from LDS one h ahead of the MFMAs that use them
-    v4i pa[TM], pb[TN];
-    auto read_frags = [&](const uint8_t* st, int h) {
+    // Packed fragments are read from LDS one h ahead of the MFMAs that use them, into two register
+    // sets used alternately.  The scheduling barriers keep the reads ahead of the MFMA block, so the
+    // LDS latency hides behind sixteen or more MFMAs.
+    v4i pa[2][TM], pb[2][TN];
+    auto read_frags = [&](const uint8_t* st, int h, int set) {
+#ifdef GD_EXP_NOLDSREAD
+        if (h >= 0) return;
+#endif
 #pragma unroll
-        for (int i = 0; i < TM; ++i) pa[i] = *reinterpret_cast<const v4i*>(st + a_row + i * 32 * BKB + foff[h]);
+        for (int i = 0; i < TM; ++i) pa[set][i] = *reinterpret_cast<const v4i*>(st + a_row + i * 32 * BKB + foff[h]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) pb[j] = *reinterpret_cast<const v4i*>(st + b_row + j * 32 * BKB + foff[h]);
+        for (int j = 0; j < TN; ++j) pb[set][j] = *reinterpret_cast<const v4i*>(st + b_row + j * 32 * BKB + foff[h]);
     };
-    read_frags(lds, 0);
+    auto compute = [&](int set) {
+        v4i alo[TM], ahi[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#ifdef GD_EXP_NOUNPACK
+            alo[i] = pa[set][i]; ahi[i] = pa[set][i];
+#else
+            alo[i] = pa[set][i] & 0x0F0F0F0F;
+            ahi[i] = (pa[set][i] >> 4) & 0x0F0F0F0F;
+#endif
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#ifdef GD_EXP_NOUNPACK
+            const v4i blo = pb[set][j], bhi = pb[set][j];
+#else
+            const v4i blo = pb[set][j] & 0x0F0F0F0F;
+            const v4i bhi = (pb[set][j] >> 4) & 0x0F0F0F0F;
+#endif
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo, acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi, acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+#ifdef GD_EXP_NOLDSREAD
+    for (int q = 0; q < 2; ++q) {
+        for (int i = 0; i < TM; ++i) pa[q][i] = v4i{lane, 1, 2, 3};
+        for (int j = 0; j < TN; ++j) pb[q][j] = v4i{3, lane, 1, 0};
+    }
+#endif
+    static_assert((NCH / 2) % 2 == 0, "the two fragment register sets alternate per h");
+    read_frags(lds, 0, 0);
 
     for (int ks = 0; ks < ksteps; ++ks) {
         const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
@@ -133,36 +178,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
 #ifndef GD_EXP_NOLOADS
         if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
 #endif
-
 #pragma unroll
         for (int h = 0; h < NCH / 2; ++h) {
-            v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                alo[i] = pa[i] & 0x0F0F0F0F;
-                ahi[i] = (pa[i] >> 4) & 0x0F0F0F0F;
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                blo[j] = pb[j] & 0x0F0F0F0F;
-                bhi[j] = (pb[j] >> 4) & 0x0F0F0F0F;
-            }
             if (h + 1 < NCH / 2) {
-                read_frags(st, h + 1);
+                read_frags(st, h + 1, (h + 1) & 1);
             } else {
                 // last h of the step: every read of this stage has been issued and consumed; pass the
-                // barrier (next stage complete and visible), start the next step's first reads, and
-                // only then run this h's MFMAs so that the LDS latency hides behind them
+                // barrier (next stage complete and visible), then start the next step's first reads
                 if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS>(); else wait_loads_and_barrier<0>();
-                if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0);
+                if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
             }
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], acc[i][j], 0, 0, 0);
-                }
+            __builtin_amdgcn_sched_barrier(0);
+            compute(h & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     __syncthreads();

@@ -190,6 +190,7 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_generic_kernel(Rotate
 int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     if (a.M == 0) return BASQ_OK;
     if (rotate_quant_pow2_applicable(a)) return launch_rotate_quant_pow2(a, s);
+    if (rotate_quant_k28_applicable(a)) return launch_rotate_quant_k28(a, s);
     int log2p = 0;
     while ((1 << log2p) < a.pow2) ++log2p;
     H28Masks masks{};

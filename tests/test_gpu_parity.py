@@ -55,6 +55,22 @@ def test_kronecker_rotation_with_h28(K):
     run_case(si.make_tiny(70, K, 100, seed=K, act="swiglu", clip=0.85), rot_size=rot)
 
 
+@pytest.mark.parametrize("M,scale", [(5, False), (2, True), (131, False)])
+def test_rotation_28x512_fast_kernel(M, scale):
+    """K = 14336 = 28 * 512 takes the specialised kernel (two waves per token, odd M leaves one idle)."""
+    sa = None
+    if scale:
+        sa = np.random.default_rng(3).uniform(0.8, 1.25, 14336).astype(np.float32)
+    run_case(si.make_tiny(M, 14336, 72, seed=M, act="swiglu", clip=0.85, n_outlier=32, outlier_scale=30.0),
+             act_scale=sa)
+
+
+@pytest.mark.parametrize("K,M", [(4096, 9), (8192, 6)])
+def test_pow2_fast_kernel_with_scale(K, M):
+    sa = np.random.default_rng(K).uniform(0.8, 1.25, K).astype(np.float32)
+    run_case(si.make_tiny(M, K, 40, seed=K + M), act_scale=sa, clip_lo=0.9, clip_hi=1.0)
+
+
 def test_asymmetric_scale_and_unequal_clips_and_layer_bias():
     cfg = si.LayerConfig("as", 0, 96, 1024, 160, 4, 20.0, 0.9, 0.02)
     lay = si.make_layer(cfg, seed=77, with_layer_bias=True)
