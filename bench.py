@@ -40,9 +40,10 @@ MEASURED_TRAFFIC = {
 def parse_args():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--steps", type=int, default=30)
     p.add_argument("--warmup", type=int, default=10)
-    p.add_argument("--config", default="C2", help="workload name from synth_inputs.CONFIGS")
+    p.add_argument("--config", default="C5",
+                   help="workload name from synth_inputs.CONFIGS (default C5: the M=4096 prefill GEMM the targets are quoted on)")
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
@@ -230,8 +231,8 @@ def main():
         "roofline_rotate_quant": roof_rq,
     }
     if not args.no_cpu_baseline and not rq_only:
-        # about 2e11 integer operations keep the oracle busy for 10-30 s on the host cores
-        sample = max(1, min(M, int(round(2e11 / (2.0 * N * K)))))
+        # about 1.5e12 integer operations keep the oracle busy for 10-30 s on the box's 16 host cores
+        sample = max(1, min(M, int(round(1.5e12 / (2.0 * N * K)))))
         out["cpu_baseline"] = cpu_baseline(cfg, lay, sample)
     print(json.dumps(out))
 

@@ -13,10 +13,17 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int GV_WAVES = 4;
+#ifndef GV_WAVES_CFG
+#define GV_WAVES_CFG 4
+#endif
+#ifndef GV_STEPS_CFG
+#define GV_STEPS_CFG 8
+#endif
+constexpr int GV_WAVES = GV_WAVES_CFG;
 constexpr int GV_THREADS = GV_WAVES * 64;
+static_assert(GV_THREADS >= 256, "the epilogue maps one thread to each of the 16 x 16 outputs");
 constexpr int GV_ROWS = 16;        // output channels per workgroup
-constexpr int GV_MAX_STEPS = 8;    // 64-byte k-chunks per wave held in registers at once
+constexpr int GV_MAX_STEPS = GV_STEPS_CFG;    // 64-byte k-chunks per wave held in registers at once
 
 __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
     __shared__ int part[GV_WAVES][GV_ROWS * 16];
@@ -32,6 +39,21 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
     const bool t_ok = row < a.M;               // the same lane index selects the token on the other operand
     const uint8_t* wrow = a.Wq + (int64_t)(n_ok ? n : 0) * KB + sub * 16;
     const uint8_t* arow = a.Aq + (int64_t)(t_ok ? row : 0) * KB + sub * 16;
+
+    // epilogue constants of the output this thread will finish (16 consecutive channels of one token per
+    // 16 threads): requested now so that their latency overlaps the weight stream
+    const int orow = tid & 15, otok = tid >> 4;
+    const int on = n0 + orow;
+    const bool out_ok = otok < a.M && on < a.N && otok < 16;
+    basq_tokmeta mt = {0.f, 0.f, 0, 0};
+    float sw = 0.f, zp = 0.f, ws = 0.f, cb = 0.f;
+    if (out_ok) {
+        mt = a.meta[otok];
+        sw = bf16_to_f32(a.w_scale[on]);
+        zp = bf16_to_f32(a.w_zero[on]);
+        ws = a.w_sum[on];
+        cb = a.out_bias ? a.out_bias[on] : 0.0f;
+    }
 
     v4i acc = {0, 0, 0, 0};
     for (int c0 = wave; c0 < nchunks; c0 += GV_WAVES * GV_MAX_STEPS) {
@@ -56,18 +78,13 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
     for (int r = 0; r < 4; ++r) part[wave][(4 * sub + r) * 16 + row] = acc[r];
     __syncthreads();
 
-    const int orow = tid & 15, otok = tid >> 4;      // 16 consecutive channels of one token per 16 threads
+    if (GV_THREADS > 256 && tid >= 256) return;
     int av = 0;
 #pragma unroll
     for (int w = 0; w < GV_WAVES; ++w) av += part[w][orow * 16 + otok];
-    const int on = n0 + orow;
-    if (otok < a.M && on < a.N) {
-        const basq_tokmeta mt = a.meta[otok];
-        const float sw = bf16_to_f32(a.w_scale[on]);
-        const float zp = bf16_to_f32(a.w_zero[on]);
-        const float cb = a.out_bias ? a.out_bias[on] : 0.0f;
+    if (out_ok) {
         const float t = (float)av - zp * (float)mt.rowsum;
-        const float y = fmaf(mt.scale * sw, t, fmaf(mt.lo, a.w_sum[on], cb));
+        const float y = fmaf(mt.scale * sw, t, fmaf(mt.lo, ws, cb));
         a.Y[(int64_t)otok * a.ldy + on] = f32_to_bf16(y);
         if (a.acc_out) a.acc_out[(int64_t)otok * a.N + on] = av;
     }

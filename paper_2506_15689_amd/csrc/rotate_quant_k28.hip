@@ -115,7 +115,7 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const int i = 8 * g + t;
-                R[t] = (i < 28) ? *reinterpret_cast<const v4u*>(xrow + i * 512 + 128 * jb) : v4u{0u, 0u, 0u, 0u};
+                R[t] = (i < 28) ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(xrow + i * 512 + 128 * jb)) : v4u{0u, 0u, 0u, 0u};
             }
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
@@ -251,8 +251,7 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
                 words[r] = ev | (od << 4);
             }
             if (row_valid && tok_valid)
-                *reinterpret_cast<uint4*>(a.Aq + m * (int64_t)(K28 / 2) + (ch0 + 32 * jb) / 2) =
-                    make_uint4(words[0], words[1], words[2], words[3]);
+                nt_store16(a.Aq + m * (int64_t)(K28 / 2) + (ch0 + 32 * jb) / 2, make_uint4(words[0], words[1], words[2], words[3]));
         }
         sum += dppi<0xB1>(sum);
         sum += dppi<0x4E>(sum);

@@ -28,7 +28,10 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 
-constexpr int P2_WAVES = 4;                 // wavefronts per workgroup
+#ifndef P2_WAVES_CFG
+#define P2_WAVES_CFG 4
+#endif
+constexpr int P2_WAVES = P2_WAVES_CFG;      // wavefronts per workgroup
 constexpr int P2_THREADS = P2_WAVES * 64;
 #ifndef P2_OCC_4096
 #define P2_OCC_4096 3
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     auto load_token = [&](int64_t m) {
         const uint16_t* x = a.X + m * a.ldx + 8 * chunk;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) raw[c] = *reinterpret_cast<const uint4*>(x + 512 * c);
+        for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
     };
 
     int64_t m = wave_id;
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                     words[w] = ev | (od << 4);
                 }
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
-                *reinterpret_cast<uint4*>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
+                nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
             }
 #endif
         sum = wave_sum_i(sum);
@@ -340,7 +343,7 @@ bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {
     const int64_t want = (a.M + P2_WAVES - 1) / P2_WAVES;
-    const int64_t resident = 256 * (a.K == 4096 ? P2_OCC_4096 : 2);  // workgroups the chip holds at once
+    const int64_t resident = 256 * (a.K == 4096 ? P2_OCC_4096 : 2) * 4 / P2_WAVES;  // workgroups the chip holds at once
     const unsigned blocks = (unsigned)(want < resident ? want : resident);   // waves loop over tokens
     const float norm = (float)(1.0 / sqrt((double)a.K));
     if (a.K == 4096) return launch_nc<8, true>(a, s, blocks, norm);
