@@ -32,6 +32,7 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // BKB: packed bytes of K per row per stage (64 -> 128 codes).  STAGES: LDS ring depth.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, int STAGES, int MINOCC>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_direct_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the body uses device-only buffer-resource types; the host pass only needs the stub
     constexpr int WAVES = WAVES_M * WAVES_N;
     constexpr int THREADS = WAVES * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -75,30 +76,38 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
     const int ksteps = KB / BKB;                              // K % (2*BKB) == 0 is checked by the launcher
 
     // ---- direct loads: load i of wave w fills LDS chunks [(i*WAVES + w)*64, +64) of a stage; the lane
-    // picks the global chunk whose swizzled position is its LDS slot.  Rows past the matrix are clamped.
-    const uint8_t* gsrc[LOADS];
+    // picks the global chunk whose swizzled position is its LDS slot.  Buffer loads: the per-lane byte
+    // offset is fixed for the whole kernel, the K advance is a scalar offset, the LDS address sits in M0 --
+    // no vector instruction is spent on addressing.  Rows past the matrix are clamped to the last row.
+    constexpr int A_LOADS = BM * NCH / (64 * WAVES);          // loads 0 .. A_LOADS-1 fetch activations, the rest weights
+    static_assert((BM * NCH) % (64 * WAVES) == 0, "A rows must fill whole wave loads");
+    const int swave = __builtin_amdgcn_readfirstlane(wave);
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Aq), 0, (int)(a.M * KB), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Wq), 0, (int)((int64_t)a.N * KB), 0x00020000);
+    int voff[LOADS];
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
         const int L = (i * WAVES + wave) * 64 + lane;
         const int row = L / NCH, cpos = L % NCH;
         const int swz = (BKB == 128) ? (row & 7) : ((row >> 1) & 3);
         const int c = cpos ^ swz;
-        if (row < BM) {
+        if (i < A_LOADS) {
             int64_t m = m0 + row;
             m = m < a.M ? m : a.M - 1;
-            gsrc[i] = a.Aq + m * KB + c * 16;
+            voff[i] = (int)(m * KB + c * 16);
         } else {
             int n = n0 + row - BM;
             n = n < a.N ? n : a.N - 1;
-            gsrc[i] = a.Wq + (int64_t)n * KB + c * 16;
+            voff[i] = (int)((int64_t)n * KB + c * 16);
         }
     }
     auto issue_loads = [&](int ks) {
-        uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES;
+        uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES + swave * 1024;
         const int koff = ks * BKB;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            __builtin_amdgcn_global_load_lds(GLB_PTR(gsrc[i] + koff), LDS_PTR(stage + (i * WAVES + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i < A_LOADS ? rsrc_a : rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16,
+                                                     voff[i], koff, 0, 0);
     };
 
     // ---- fragment addressing: lane (frow, fhalf) reads chunk fhalf + 2h of its row, swizzled
@@ -242,6 +251,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
             }
         }
     }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BKB, int STAGES, int MINOCC>
@@ -256,7 +266,10 @@ int launch_direct(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
-bool gemm_direct_applicable(const GemmArgs& a) { return a.K % 256 == 0 && a.M >= 1; }
+bool gemm_direct_applicable(const GemmArgs& a) {
+    // buffer addressing: both packed operands must be smaller than 4 GiB
+    return a.K % 256 == 0 && a.M >= 1 && a.M * (a.K / 2) < 0xFFFFFFFFll && (int64_t)a.N * (a.K / 2) < 0xFFFFFFFFll;
+}
 
 namespace {
 // share of the launched tile slots that hold a real tile when `tiles` tiles run `slots` at a time
