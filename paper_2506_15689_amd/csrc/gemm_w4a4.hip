@@ -125,26 +125,14 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_w4a4_kernel(GemmA
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const v4i x = *reinterpret_cast<const v4i*>(st + a_off + i * 32 * LDS_ROW + h * 32);
-#if defined(GEMM_EXP_NOUNPACK)
-                alo[i] = x; ahi[i] = x;
-#elif defined(GEMM_EXP_2OP)
-                alo[i] = x & 0x0F0F0F0F; ahi[i] = x & (int)0xF0F0F0F0;
-#else
                 alo[i] = x & 0x0F0F0F0F;
                 ahi[i] = (x >> 4) & 0x0F0F0F0F;
-#endif
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const v4i x = *reinterpret_cast<const v4i*>(st + b_off + j * 32 * LDS_ROW + h * 32);
-#if defined(GEMM_EXP_NOUNPACK)
-                const v4i blo = x, bhi = x;
-#elif defined(GEMM_EXP_2OP)
-                const v4i blo = x & (int)0xF0F0F0F0, bhi = x & 0x0F0F0F0F;
-#else
                 const v4i blo = x & 0x0F0F0F0F;
                 const v4i bhi = (x >> 4) & 0x0F0F0F0F;
-#endif
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo, acc[i][j], 0, 0, 0);
@@ -192,11 +180,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_w4a4_kernel(GemmA
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WN + j * 32 + col_in_tile;
-#ifdef GEMM_EXP_NOEPI
-                if (n < a.N && acc[i][j][r] == 0x7fffffff) {
-#else
                 if (n < a.N) {
-#endif
                     const int av = acc[i][j][r];
                     const float t = (float)av - cp[j].y * rp.z;
                     const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));

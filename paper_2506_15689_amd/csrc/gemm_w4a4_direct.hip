@@ -22,11 +22,7 @@ constexpr int NUM_XCD = 8;
 // barrier would first wait for ALL outstanding loads, which would serialise the LDS ring.
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
-#ifdef GD_EXP_NOBARRIER
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-#else
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-#endif
 }
 
 // BKB: packed bytes of K per row per stage (64 -> 128 codes).  STAGES: LDS ring depth.
@@ -138,9 +134,6 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
     // LDS latency hides behind sixteen or more MFMAs.
     v4i pa[2][TM], pb[2][TN];
     auto read_frags = [&](const uint8_t* st, int h, int set) {
-#ifdef GD_EXP_NOLDSREAD
-        if (h >= 0) return;
-#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i) pa[set][i] = *reinterpret_cast<const v4i*>(st + a_row + i * 32 * BKB + foff[h]);
 #pragma unroll
@@ -150,21 +143,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
         v4i alo[TM], ahi[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-#ifdef GD_EXP_NOUNPACK
-            alo[i] = pa[set][i]; ahi[i] = pa[set][i];
-#else
             alo[i] = pa[set][i] & 0x0F0F0F0F;
             ahi[i] = (pa[set][i] >> 4) & 0x0F0F0F0F;
-#endif
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-#ifdef GD_EXP_NOUNPACK
-            const v4i blo = pb[set][j], bhi = pb[set][j];
-#else
             const v4i blo = pb[set][j] & 0x0F0F0F0F;
             const v4i bhi = (pb[set][j] >> 4) & 0x0F0F0F0F;
-#endif
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo, acc[i][j], 0, 0, 0);
@@ -172,21 +157,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
             }
         }
     };
-#ifdef GD_EXP_NOLDSREAD
-    for (int q = 0; q < 2; ++q) {
-        for (int i = 0; i < TM; ++i) pa[q][i] = v4i{lane, 1, 2, 3};
-        for (int j = 0; j < TN; ++j) pb[q][j] = v4i{3, lane, 1, 0};
-    }
-#endif
     static_assert((NCH / 2) % 2 == 0, "the two fragment register sets alternate per h");
     read_frags(lds, 0, 0);
 
     for (int ks = 0; ks < ksteps; ++ks) {
         const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
         // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
-#ifndef GD_EXP_NOLOADS
         if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
-#endif
 #pragma unroll
         for (int h = 0; h < NCH / 2; ++h) {
             if (h + 1 < NCH / 2) {
@@ -225,6 +202,56 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
     float4 cp[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
+
+    // Vector path: each wave turns one 32-row block of its tile at a time into bf16 in a private LDS
+    // patch (row pitch padded against bank conflicts) and writes it out as 16-byte pieces, whole rows of
+    // the wave tile contiguous.  Needs 16-byte aligned rows of Y; the debug accumulator dump and
+    // unaligned outputs take the scalar path below.
+    const bool vec_ok = a.acc_out == nullptr && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
+    if (vec_ok) {
+        constexpr int PITCH = WN * 2 + 16;                      // bytes
+        constexpr int CH_PER_ROW = WN / 8;                      // 16-byte pieces per row
+        constexpr int PIECES = 32 * CH_PER_ROW / 64;            // per lane per 32-row block
+        uint8_t* patch = lds + (BM + BN) * 16 + wave * (32 * PITCH);
+        static_assert((BM + BN) * 16 + WAVES * 32 * PITCH <= STAGES * STAGE_BYTES, "epilogue staging does not fit");
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
+                const float4 rp = lrow_par[wm * WM + i * 32 + rloc];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const float t = (float)acc[i][j][r] - cp[j].y * rp.z;
+                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
+                    *reinterpret_cast<uint16_t*>(patch + rloc * PITCH + (j * 32 + col_in_tile) * 2) = f32_to_bf16(y);
+                }
+            }
+            // one wave's LDS operations complete in order: the reads below see the writes above
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < PIECES; ++q) {
+                const int id = q * 64 + lane;
+                const int rloc = id / CH_PER_ROW, ch = id % CH_PER_ROW;
+                const uint4 v = *reinterpret_cast<const uint4*>(patch + rloc * PITCH + ch * 16);
+                const int64_t m = m0 + wm * WM + i * 32 + rloc;
+                const int n = n0 + wn * WN + ch * 8;
+                if (m < a.M) {
+                    uint16_t* dst = a.Y + m * a.ldy + n;
+                    if (n + 8 <= a.N) {
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    } else {
+                        const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                               (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) if (n + u < a.N) dst[u] = e[u];
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -237,11 +264,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WN + j * 32 + col_in_tile;
-#ifdef GD_EXP_NOEPI
-                if (n < a.N && acc[i][j][r] == 0x7fffffff) {
-#else
                 if (n < a.N) {
-#endif
                     const int av = acc[i][j][r];
                     const float t = (float)av - cp[j].y * rp.z;
                     const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));

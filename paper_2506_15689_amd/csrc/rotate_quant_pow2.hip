@@ -131,11 +131,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
         }
     }
     // global load: chunk bits (e3,e4,e5,e6,e7,e8) <- lane bits (2,3,0,1,4,5)
-#ifdef P2_EXP_LINEAR_CHUNK
-    const int chunk = lane;
-#else
     const int chunk = ((lane >> 2) & 3) | ((lane & 3) << 2) | (lane & 0x30);
-#endif
     // LDS write base (words), lane bits (0..5) = (e1,e2,e7,e8,e3,e4); address map at the transpose below
     const int wbase = ((lane & 15) << 1) | (((lane >> 4) & 3) << 7);
     // LDS read base: lane bits (0..5) = (e5..e10)
@@ -208,9 +204,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                         const int r0 = r & 1, r1 = r >> 1;
                         const int addr = (wbase ^ ((r0 << 1) | (r1 << 2))) | (r0 << 5) | (r1 << 6) | (c01 << 9);
                         const int c = 8 * hf + 4 * c2 + c01;
-#ifndef P2_EXP_NOLDS
                         *reinterpret_cast<float2*>(wl + addr) = make_float2(d[c][0][r], d[c][1][r]);
-#endif
                     }
                 // LDS serves one wave's instructions in issue order: the reads below see these writes,
                 // and the next round's writes do not overtake these reads
@@ -219,11 +213,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                 for (int q = 0; q < 16; ++q) {
                     const int e1 = q & 1, e2 = (q >> 1) & 1, e3 = (q >> 2) & 1, e4 = q >> 3;
                     const int addr = (rbase ^ ((e1 << 1) | (e2 << 2))) | (e3 << 7) | (e4 << 8);
-#ifndef P2_EXP_NOLDS
                     const float2 v = *reinterpret_cast<const float2*>(wl + addr);
-#else
-                    const float2 v = make_float2(d[8 * hf + 4 * c2 + (q & 3)][0][q >> 2], d[8 * hf + 4 * c2 + (q & 3)][1][q >> 2]);
-#endif
                     const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
                     p[hf][c2][idx] = v.x;
                     p[hf][c2][idx | 1] = v.y;
@@ -284,7 +274,6 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
 
         // ---- quantise, pack, store -----------------------------------------------------------------
         int sum = 0;
-#ifndef P2_EXP_NOQUANT
 #pragma unroll
         for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
@@ -307,7 +296,6 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
             }
-#endif
         sum = wave_sum_i(sum);
         if (lane == 0) {
             basq_tokmeta mt;

@@ -157,6 +157,27 @@ def test_strided_input_and_output():
     assert (Ybig[:, 48:] == 0).all()
 
 
+def test_output_width_not_a_multiple_of_eight():
+    """N = 100 written into rows of 104 (16-byte aligned rows, ragged last piece) and into rows of 100
+    (unaligned rows): both must equal the reference path that also dumps the accumulators."""
+    dev = "cuda"
+    lay = si.make_tiny(70, 512, 100, seed=51)
+    case = pu.make_case(lay)
+    d = pu.to_device(case)
+    g = pu.run_gpu(case, d)
+    pu.check_parity(case, g)
+    Aq, meta = B.alloc_activation_buffers(70, 512, dev)
+    B.basq_rotate_quant(d.X, 512, d.bias, None, case.clip_lo, case.clip_hi, Aq, meta)
+    Ywide = torch.zeros((70, 104), dtype=torch.bfloat16, device=dev)
+    Ytight = torch.zeros((70, 100), dtype=torch.bfloat16, device=dev)
+    B.basq_w4a4_gemm(Aq, meta, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Ywide[:, :100])
+    B.basq_w4a4_gemm(Aq, meta, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Ytight)
+    torch.cuda.synchronize()
+    ref = si.bits_to_bf16(g.y_bits).to(dev)
+    assert torch.equal(Ywide[:, :100], ref) and torch.equal(Ytight, ref)
+    assert (Ywide[:, 100:] == 0).all()
+
+
 def test_same_input_twice_gives_identical_bits():
     lay = si.make_tiny(300, 1024, 200, seed=41)
     case = pu.make_case(lay)
