@@ -46,6 +46,7 @@ def parse_args():
                    help="workload name from synth_inputs.CONFIGS (default C5: the M=4096 prefill GEMM the targets are quoted on)")
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling diagnostics")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy three times (scales the HBM byte counters of a profiler run)")
@@ -198,6 +199,31 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- measured ceilings of this machine (diagnostic kernels of the library; a few milliseconds) ------
+    ceilings = {}
+    if not args.no_ceilings:
+        ct = max(M, 32768)                                  # enough tokens to reach the streaming asymptote
+        csrc = torch.empty(ct * 2 * K, dtype=torch.uint8, device=dev).fill_(1)
+        cdst = torch.empty(ct * (K // 2), dtype=torch.uint8, device=dev)
+        cmeta = torch.empty(ct * 16, dtype=torch.uint8, device=dev)
+
+        def stream_once(i):
+            B.basq_diag_stream(csrc, cdst, cmeta, ct, K, stream=stream)
+        for i in range(3):
+            stream_once(i)
+        ms, _ = timed(stream_once, 10)
+        ceilings["hbm_stream_GBps"] = ct * (2 * K + K // 2 + 16) / (ms * 1e-3) / 1e9
+        del csrc, cdst, cmeta
+        cout = torch.empty(512 * 256, dtype=torch.int32, device=dev)
+        iters = 2000
+
+        def mfma_once(i):
+            B.basq_diag_mfma_i8(cout, 512, iters, stream=stream)
+        mfma_once(0)
+        ms, _ = timed(mfma_once, 3)
+        ceilings["int8_mfma_TOPS"] = 512 * 4 * 8 * iters * 65536.0 / (ms * 1e-3) / 1e12
+        del cout
+
     rq_bytes = algorithmic_bytes_rotate_quant(M, K)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
@@ -217,6 +243,16 @@ def main():
     roof_rq = {"kernel": "rotate_quant", "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                "frac": rq_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "rotate_quant")),
                "algorithmic_bytes": rq_bytes, "avg_kernel_ms": rq_ms}
+
+    if ceilings:
+        roof_rq["measured_ceiling"] = ceilings["hbm_stream_GBps"]
+        roof_rq["frac_of_measured_ceiling"] = rq_gbs / ceilings["hbm_stream_GBps"]
+        if roof is not None and roof["bound"] == "mfma":
+            roof["measured_ceiling"] = ceilings["int8_mfma_TOPS"]
+            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["int8_mfma_TOPS"]
+        elif roof is not None:
+            roof["measured_ceiling"] = ceilings["hbm_stream_GBps"]
+            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["hbm_stream_GBps"]
 
     out = {
         "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",

@@ -159,6 +159,22 @@ int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_
  * int8 (Paley type-I construction over GF(27) = GF(3)[t]/(t^3 + 2t + 1)). */
 int basq_hadamard28(int8_t* out_host);
 
+/* ---- diagnostics: what this machine sustains (used by the benchmark's measured ceilings) ---------- */
+
+/*
+ * Pure streaming kernel with the access pattern of basq_rotate_quant (the paper's fused quant kernel,
+ * Fig. 6, is bandwidth bound): one wavefront per token reads 2K bytes from src + m*2K and writes K/2
+ * bytes to dst + m*K/2 and 16 bytes to meta + m*16.  K a multiple of 2048.  Moves tokens*(2.5K+16) bytes.
+ */
+int basq_diag_stream(const void* src, void* dst, void* meta, int64_t tokens, int32_t K, void* stream);
+
+/*
+ * Register-resident int8 MFMA loop (Sec. 5.2: the prefill GEMM is compute bound): `blocks` workgroups of
+ * 4 waves, each wave issues 8*iters v_mfma_i32_32x32x32_i8 on 4-bit valued operands; out receives
+ * blocks*256 int32 checksums.  Executes blocks*4*8*iters*65536 integer operations.
+ */
+int basq_diag_mfma_i8(int32_t* out, int32_t blocks, int32_t iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

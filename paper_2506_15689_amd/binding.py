@@ -21,7 +21,7 @@ BASQ_W_CANONICAL = 0
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
            "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
-           "basq_hadamard28"]
+           "basq_hadamard28", "basq_diag_stream", "basq_diag_mfma_i8"]
 
 
 class BasqError(RuntimeError):
@@ -65,6 +65,10 @@ def load() -> ctypes.CDLL:
     lib.basq_calibrate_bias.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, c.c_size_t, vp]
     lib.basq_hadamard28.restype = c.c_int
     lib.basq_hadamard28.argtypes = [vp]
+    lib.basq_diag_stream.restype = c.c_int
+    lib.basq_diag_stream.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.basq_diag_mfma_i8.restype = c.c_int
+    lib.basq_diag_mfma_i8.argtypes = [vp, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -158,6 +162,15 @@ def basq_calibrate_bias(X: torch.Tensor, rot_size: int, act_scale: Optional[torc
     _check(load().basq_calibrate_bias(_p(X), M, K, X.stride(0), rot_size, _p(act_scale), _p(bias_out),
                                       _p(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream)))
+
+
+def basq_diag_stream(src: torch.Tensor, dst: torch.Tensor, meta: torch.Tensor, tokens: int, K: int, *,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    _check(load().basq_diag_stream(_p(src), _p(dst), _p(meta), tokens, K, _stream(stream)))
+
+
+def basq_diag_mfma_i8(out: torch.Tensor, blocks: int, iters: int, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    _check(load().basq_diag_mfma_i8(_p(out), blocks, iters, _stream(stream)))
 
 
 # ---- allocation helpers (device memory only; no arithmetic) ----------------------------------
