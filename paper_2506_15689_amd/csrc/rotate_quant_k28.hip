@@ -24,8 +24,8 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 constexpr int K28 = 14336;
-constexpr int K28_WAVES = 4;                     // two tokens per workgroup
-constexpr int K28_THREADS = K28_WAVES * 64;
+// Workgroups of four waves (two tokens), two per compute unit, while one 64 KB vector (b^c or s^a) is
+// staged in LDS; with both vectors staged, eight waves (four tokens) and one workgroup per unit.
 
 struct H28Cols {
     uint32_t col[28];   // bit i of col[j] set  <=>  H28[i][j] == -1
@@ -59,12 +59,21 @@ __device__ __forceinline__ void cross_lane_bfly(float& x, float& y) {
     y = fa - fb;
 }
 
-template <bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
-__global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(RotateQuantArgs a, float norm, H28Cols hc) {
-    // bias laid out so that for a piece index q the 64 lanes of a wave half read consecutive float4s
-    constexpr int BIAS_WORDS = HAS_BIAS ? 2 * 32 * 64 * 4 : 0;
-    __shared__ __attribute__((aligned(16))) float lds[BIAS_WORDS + 64];
-    float* red = lds + BIAS_WORDS;                 // [token in block][half][mn, mx, sum]
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the global
+// loads of the next token and for the code stores, which nothing on the other side of the barrier reads.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int K28_WAVES, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
+__global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k28_kernel(RotateQuantArgs a, float norm, H28Cols hc) {
+    // bias (and s^a) laid out so that for a piece index q the 64 lanes of a wave half read consecutive float4s
+    constexpr int K28_THREADS = K28_WAVES * 64;
+    constexpr int VEC_WORDS = 2 * 32 * 64 * 4;
+    constexpr int BIAS_WORDS = HAS_BIAS ? VEC_WORDS : 0;
+    constexpr int SCALE_WORDS = HAS_SCALE ? VEC_WORDS : 0;
+    __shared__ __attribute__((aligned(16))) float lds[BIAS_WORDS + SCALE_WORDS + 64];
+    float* red = lds + BIAS_WORDS + SCALE_WORDS;   // [parity][token in block][half][mn, mx, sum, -]
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = wave & 1, tok_in_blk = wave >> 1;
@@ -72,17 +81,21 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
     const int ip = 16 * half + m16;                // output row i'
     const bool row_valid = ip < 28;
 
-    if (HAS_BIAS) {
+    if (HAS_BIAS || HAS_SCALE) {
         float4* dst = reinterpret_cast<float4*>(lds);
         for (int f = threadIdx.x; f < 2 * 32 * 64; f += K28_THREADS) {
             const int ln = f & 63, q = (f >> 6) & 31, hh = f >> 11;
             const int row = 16 * hh + (ln & 15);
             const int ch = row * 512 + 128 * (ln >> 4) + 4 * q;
-            dst[f] = row < 28 ? *reinterpret_cast<const float4*>(a.bias + ch) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (HAS_BIAS)
+                dst[f] = row < 28 ? *reinterpret_cast<const float4*>(a.bias + ch) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (HAS_SCALE)
+                dst[BIAS_WORDS / 4 + f] = row < 28 ? *reinterpret_cast<const float4*>(a.act_scale + ch) : make_float4(1.f, 1.f, 1.f, 1.f);
         }
     }
     __syncthreads();
     const float4* lbias = reinterpret_cast<const float4*>(lds) + half * 32 * 64;
+    const float4* lscale = reinterpret_cast<const float4*>(lds + BIAS_WORDS) + half * 32 * 64;
 
     // B operand: H_28[k = 8g + t][n = ip], zero outside 28 x 28
     v8bf bop;
@@ -100,23 +113,41 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
         bop = __builtin_bit_cast(v8bf, tmp);
     }
 
+    // 16-byte loads of column block jb of a token: rows 8g .. 8g+7 (rows >= 28 read as zero)
+    auto load_block = [&](v4u (&R)[8], int64_t tok, int jb) {
+        const uint16_t* xrow = a.X + tok * a.ldx + 8 * m16 + 128 * jb;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int i = 8 * g + t;
+            R[t] = (i < 28) ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(xrow + i * 512)) : v4u{0u, 0u, 0u, 0u};
+        }
+    };
+
     const int tokens_per_round = gridDim.x * (K28_WAVES / 2);
-    for (int64_t m0 = (int64_t)blockIdx.x * (K28_WAVES / 2); m0 < a.M; m0 += tokens_per_round) {
+    const int64_t m_first = (int64_t)blockIdx.x * (K28_WAVES / 2);
+    v4u R[4][8];
+    {
+        const int64_t m = m_first + tok_in_blk;
+        load_block(R[0], m < a.M ? m : a.M - 1, 0);
+    }
+    // The row sums of the two halves meet one token late, at the next token's barrier, so that a token
+    // costs one barrier: red is double buffered by token parity.
+    int parity = 0;
+    int64_t prev_m = -1;
+    float prev_s = 0.f, prev_lo = 0.f;
+    for (int64_t m0 = m_first; m0 < a.M; m0 += tokens_per_round, parity ^= 1) {
         const int64_t m = m0 + tok_in_blk;
         const bool tok_valid = m < a.M;
         const int64_t mm = tok_valid ? m : a.M - 1;      // keep every wave on the same barrier schedule
 
-        // ---- H_28 on the matrix core ---------------------------------------------------------------
+        // ---- H_28 on the matrix core.  Block 0 was requested one token ago; blocks 1..3 are requested
+        // together now, while the accumulators that will replace them are not live yet.
         float d[4][8][4];                                  // [jb][jj][r]
-        const uint16_t* xrow = a.X + mm * a.ldx + 8 * m16;
+#pragma unroll
+        for (int jb = 1; jb < 4; ++jb) load_block(R[jb], mm, jb);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) {
-            v4u R[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int i = 8 * g + t;
-                R[t] = (i < 28) ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(xrow + i * 512 + 128 * jb)) : v4u{0u, 0u, 0u, 0u};
-            }
 #pragma unroll
             for (int jj = 0; jj < 8; ++jj) {
                 v4u A;
@@ -124,14 +155,20 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     // bytes of (hi, lo) = (R[2u+1][w], R[2u][w]); even jj takes the low halves, odd jj the high halves
-                    A[u] = (jj & 1) ? __builtin_amdgcn_perm(R[2 * u + 1][w], R[2 * u][w], 0x07060302u)
-                                    : __builtin_amdgcn_perm(R[2 * u + 1][w], R[2 * u][w], 0x05040100u);
+                    A[u] = (jj & 1) ? __builtin_amdgcn_perm(R[jb][2 * u + 1][w], R[jb][2 * u][w], 0x07060302u)
+                                    : __builtin_amdgcn_perm(R[jb][2 * u + 1][w], R[jb][2 * u][w], 0x05040100u);
                 }
                 v4f acc = {0.f, 0.f, 0.f, 0.f};
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, A), bop, acc, 0, 0, 0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) d[jb][jj][r] = acc[r];
             }
+        }
+        // first block of this wave's next token: its latency hides behind the butterflies below
+        {
+            const int64_t mn_tok = m + tokens_per_round;
+            load_block(R[0], mn_tok < a.M ? mn_tok : a.M - 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- H_512: register stages jj (j0..2), r (j3..4), jb (j7..8) ------------------------------------
@@ -185,7 +222,7 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
                     const int c = 32 * jb + 8 * r + 4 * q2;
                     float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
                     if (HAS_BIAS) bb = lbias[(c >> 2) * 64 + lane];
-                    if (HAS_SCALE && row_valid) ss = *reinterpret_cast<const float4*>(a.act_scale + ch0 + c);
+                    if (HAS_SCALE) ss = lscale[(c >> 2) * 64 + lane];
                     const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
                     const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
                     float rr[4];
@@ -217,11 +254,19 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
             mn = fminf(fminf(lo4[0], lo4[1]), fminf(lo4[2], lo4[3]));
             mx = fmaxf(fmaxf(hi4[0], hi4[1]), fmaxf(hi4[2], hi4[3]));
         }
-        float* myred = red + tok_in_blk * 8;
+        float* myred = red + (parity * (K28_WAVES / 2) + tok_in_blk) * 8;
+        float* otherred = red + ((parity ^ 1) * (K28_WAVES / 2) + tok_in_blk) * 8;
         if (lane == 0) { myred[half * 4 + 0] = mn; myred[half * 4 + 1] = mx; }
-        __syncthreads();
+        lds_barrier();
         mn = fminf(myred[0], myred[4]);
         mx = fmaxf(myred[1], myred[5]);
+        if (half == 0 && lane == 0 && prev_m >= 0) {       // finish the previous token
+            basq_tokmeta mt;
+            mt.scale = prev_s; mt.lo = prev_lo;
+            mt.rowsum = reinterpret_cast<int*>(otherred)[2] + reinterpret_cast<int*>(otherred)[6];
+            mt.reserved = 0;
+            a.meta[prev_m] = mt;
+        }
 
         const float lo = a.clip_lo * mn;
         const float hi = a.clip_hi * mx;
@@ -260,24 +305,31 @@ __global__ __launch_bounds__(K28_THREADS, 2) void rotate_quant_k28_kernel(Rotate
         sum = __builtin_amdgcn_readlane(sum, 0) + __builtin_amdgcn_readlane(sum, 16) +
               __builtin_amdgcn_readlane(sum, 32) + __builtin_amdgcn_readlane(sum, 48);
         if (lane == 0) reinterpret_cast<int*>(myred)[half * 4 + 2] = sum;
-        __syncthreads();
-        if (half == 0 && lane == 0 && tok_valid) {
-            basq_tokmeta mt;
-            mt.scale = s; mt.lo = lo;
-            mt.rowsum = reinterpret_cast<int*>(myred)[2] + reinterpret_cast<int*>(myred)[6];
-            mt.reserved = 0;
-            a.meta[m] = mt;
-        }
-        __syncthreads();                               // red is rewritten by the next token
+        prev_m = tok_valid ? m : -1;
+        prev_s = s; prev_lo = lo;
+    }
+    lds_barrier();
+    if (half == 0 && lane == 0 && prev_m >= 0) {
+        const int* lastred = reinterpret_cast<const int*>(red + ((parity ^ 1) * (K28_WAVES / 2) + tok_in_blk) * 8);
+        basq_tokmeta mt;
+        mt.scale = prev_s; mt.lo = prev_lo;
+        mt.rowsum = lastred[2] + lastred[6];
+        mt.reserved = 0;
+        a.meta[prev_m] = mt;
     }
 }
 
 template <bool HB, bool HS>
-int launch_k28_flags(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm, const H28Cols& hc) {
+int launch_k28_flags(const RotateQuantArgs& a, hipStream_t s, float norm, const H28Cols& hc) {
+    constexpr int WAVES = (HB && HS) ? 8 : 4;
+    constexpr int TOKENS = WAVES / 2;
+    constexpr int MAX_BLOCKS = 256 * (8 / WAVES);
+    const int64_t want = (a.M + TOKENS - 1) / TOKENS;
+    const unsigned blocks = (unsigned)(want < MAX_BLOCKS ? want : MAX_BLOCKS);
     if (a.rot_out)
-        hipLaunchKernelGGL((rotate_quant_k28_kernel<HB, HS, true>), dim3(blocks), dim3(K28_THREADS), 0, s, a, norm, hc);
+        hipLaunchKernelGGL((rotate_quant_k28_kernel<WAVES, HB, HS, true>), dim3(blocks), dim3(WAVES * 64), 0, s, a, norm, hc);
     else
-        hipLaunchKernelGGL((rotate_quant_k28_kernel<HB, HS, false>), dim3(blocks), dim3(K28_THREADS), 0, s, a, norm, hc);
+        hipLaunchKernelGGL((rotate_quant_k28_kernel<WAVES, HB, HS, false>), dim3(blocks), dim3(WAVES * 64), 0, s, a, norm, hc);
     return check_hip(hipGetLastError(), "rotate_quant (28x512) launch");
 }
 
@@ -295,14 +347,12 @@ int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s) {
         for (int i = 0; i < 28; ++i) if (h[i * 28 + j] < 0) mk |= 1u << i;
         hc.col[j] = mk;
     }
-    const int64_t want = (a.M + 1) / 2;
-    const unsigned blocks = (unsigned)(want < 512 ? want : 512);
     const float norm = (float)(1.0 / sqrt((double)K28));
     const bool hb = a.bias != nullptr, hs = a.act_scale != nullptr;
-    if (hb && hs) return launch_k28_flags<true, true>(a, s, blocks, norm, hc);
-    if (hb) return launch_k28_flags<true, false>(a, s, blocks, norm, hc);
-    if (hs) return launch_k28_flags<false, true>(a, s, blocks, norm, hc);
-    return launch_k28_flags<false, false>(a, s, blocks, norm, hc);
+    if (hb && hs) return launch_k28_flags<true, true>(a, s, norm, hc);
+    if (hb) return launch_k28_flags<true, false>(a, s, norm, hc);
+    if (hs) return launch_k28_flags<false, true>(a, s, norm, hc);
+    return launch_k28_flags<false, false>(a, s, norm, hc);
 }
 
 }  // namespace basq

@@ -55,9 +55,10 @@ def test_kronecker_rotation_with_h28(K):
     run_case(si.make_tiny(70, K, 100, seed=K, act="swiglu", clip=0.85), rot_size=rot)
 
 
-@pytest.mark.parametrize("M,scale", [(5, False), (2, True), (131, False)])
+@pytest.mark.parametrize("M,scale", [(5, False), (2, True), (131, False), (11, True), (1030, True)])
 def test_rotation_28x512_fast_kernel(M, scale):
-    """K = 14336 = 28 * 512 takes the specialised kernel (two waves per token, odd M leaves one idle)."""
+    """K = 14336 = 28 * 512 takes the specialised kernel: two waves per token, two tokens per workgroup
+    (four when s^a is staged next to b^c); ragged M leaves waves idle, M = 1030 needs a second round."""
     sa = None
     if scale:
         sa = np.random.default_rng(3).uniform(0.8, 1.25, 14336).astype(np.float32)
