@@ -276,9 +276,9 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         const float nlo = -(lo * inv);
 
         int sum = 0;
+        uint32_t words[4][4];                              // [jb][r]: 16 bytes of codes per jb
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) {
-            uint32_t words[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 uint32_t ev = 0, od = 0;
@@ -293,10 +293,26 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                     sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
                     sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
                 }
-                words[r] = ev | (od << 4);
+                words[jb][r] = ev | (od << 4);
             }
-            if (row_valid && tok_valid)
-                nt_store16(a.Aq + m * (int64_t)(K28 / 2) + (ch0 + 32 * jb) / 2, make_uint4(words[0], words[1], words[2], words[3]));
+        }
+        // A lane holds 64 consecutive output bytes as four 16-byte pieces.  Transposing the pieces over
+        // (jb, g) lets every store instruction write whole 64-byte segments (piece jb of lane g goes to
+        // register g of lane jb), instead of four partial writes per segment.
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            auto s0 = __builtin_amdgcn_permlane16_swap(words[0][r], words[1][r], false, false);
+            auto s1 = __builtin_amdgcn_permlane16_swap(words[2][r], words[3][r], false, false);
+            auto t0 = __builtin_amdgcn_permlane32_swap(s0[0], s1[0], false, false);
+            auto t1 = __builtin_amdgcn_permlane32_swap(s0[1], s1[1], false, false);
+            words[0][r] = t0[0]; words[2][r] = t0[1];
+            words[1][r] = t1[0]; words[3][r] = t1[1];
+        }
+        if (row_valid && tok_valid) {
+            uint8_t* orow = a.Aq + m * (int64_t)(K28 / 2) + ip * 256 + 16 * g;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                nt_store16(orow + 64 * j, make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]));
         }
         sum += dppi<0xB1>(sum);
         sum += dppi<0x4E>(sum);
