@@ -1,0 +1,344 @@
+// Prefill INT4 x INT4 -> INT32 GEMM on the f8f6f4 matrix-core path (paper Sec. 5.2; Fig. 6; Eq. 14).
+//
+// Both operands arrive in the fp6 operand form of fp6_pack.hip: code q stored as the e2m3 number
+// q - 7.5.  v_mfma_f32_32x32x64_f8f6f4 with two fp6 operands runs at twice the int8 rate and its fp32
+// accumulator holds S = sum_k (qa - 7.5)(qb - 7.5) exactly (multiples of 1/4, |S| < 2^21 for K <= 32768).
+// The epilogue restores the integer accumulator of the INT4 product,
+//     ACC = (4S + 30*rowsum_m + 30*codesum_n - 225*K) / 4        (all integers, the division exact),
+// and de-quantises exactly as the int8 kernels do.
+//
+// Structure as in gemm_w4a4_direct.hip: direct-to-LDS buffer loads into a ring of stages, fragments
+// read one step ahead into two register sets, XCD-aware tile order.  A stage holds 128 codes per row.
+// The operands are stored as 3 KB blocks of 32 rows x 128 codes that already are the LDS image (see
+// fp6_pack.hip): a stage is filled by contiguous 1 KB copies of whole cache lines, and both the 16-byte
+// and the 8-byte fragment reads are free of bank conflicts.  No unpacking: LDS -> registers -> MFMA.
+#include "basq_internal.h"
+
+namespace basq {
+
+namespace {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int NUM_XCD = 8;
+constexpr int CHUNK = 96;              // bytes of one row per stage: 128 codes
+constexpr int BLOCK = 32 * CHUNK;      // one 32-row block of a stage: 2 KB of 16-byte pieces, 1 KB of 8-byte tails
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// Wait until at most N of this wave's direct-to-LDS loads are outstanding and its own LDS reads have
+// returned, then join the workgroup barrier (one asm block: the compiler's own barrier would wait for
+// every outstanding load and serialise the ring).
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+#ifndef G6_GROUP_M
+#define G6_GROUP_M 4
+#endif
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MINOCC>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the body uses device-only buffer-resource types; the host pass only needs the stub
+    constexpr int WAVES = WAVES_M * WAVES_N;
+    constexpr int THREADS = WAVES * 64;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int ROWS = BM + BN;
+    constexpr int STAGE_BYTES = ROWS * CHUNK;
+    constexpr int LOADS = STAGE_BYTES / (WAVES * 1024);       // direct loads (1 KB per wave) per thread per stage
+    constexpr int A_LOADS = BM * CHUNK / (WAVES * 1024);      // loads 0 .. A_LOADS-1 fetch activations
+    static_assert(STAGE_BYTES % (WAVES * 1024) == 0 && (BM * CHUNK) % (WAVES * 1024) == 0, "stage does not divide over the waves");
+    static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32-row blocks");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+    static_assert(STAGES == 2 || STAGES == 3, "the wait counts below assume at most one stage in flight beyond the next");
+
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[STAGES * STAGE_BYTES];
+
+    // ---- tile assignment (XCD-aware: ids congruent mod 8 run on one XCD and walk a compact band)
+    int tile_m, tile_n;
+    {
+        const int total = tiles_m * tiles_n;
+        const int pid = blockIdx.x;
+        int t = pid;
+        const int per_xcd = total / NUM_XCD;
+        if (pid < per_xcd * NUM_XCD) t = (pid % NUM_XCD) * per_xcd + pid / NUM_XCD;
+        constexpr int GROUP_M = G6_GROUP_M;
+        const int band = t / (GROUP_M * tiles_n);
+        const int first_m = band * GROUP_M;
+        const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+        const int in_band = t - band * GROUP_M * tiles_n;
+        tile_m = first_m + in_band % rows;
+        tile_n = in_band / rows;
+    }
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
+    const int ksteps = a.K / 128;
+    const int rb_a = (int)((a.M + 31) >> 5), rb_w = (a.N + 31) >> 5;   // 32-row blocks per chunk of K
+    const unsigned a_step = (unsigned)rb_a * BLOCK, w_step = (unsigned)rb_w * BLOCK;   // bytes from one chunk of K to the next
+
+    // ---- direct loads: load i of wave w copies the 1 KB piece number i*WAVES + w of the stage; three
+    // pieces make one 32-row block.  Blocks past the matrix are clamped to its last block.
+    const int swave = __builtin_amdgcn_readfirstlane(wave);
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Aq6), 0, (int)(a_step * (unsigned)ksteps), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Wq6), 0, (int)(w_step * (unsigned)ksteps), 0x00020000);
+    int voff[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int piece = i * WAVES + wave;
+        int blk = piece / 3;
+        const int part = piece % 3;
+        if (i < A_LOADS) {
+            blk += (int)(m0 >> 5);
+            blk = blk < rb_a ? blk : rb_a - 1;
+        } else {
+            blk += (n0 >> 5) - BM / 32;
+            blk = blk < rb_w ? blk : rb_w - 1;
+        }
+        voff[i] = blk * BLOCK + part * 1024 + lane * 16;
+    }
+    auto issue_loads = [&](int ks) {
+        uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES + swave * 1024;
+        const int koff_a = (int)((unsigned)ks * a_step), koff_w = (int)((unsigned)ks * w_step);   // unsigned 32-bit byte offsets
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i < A_LOADS ? rsrc_a : rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16,
+                                                     voff[i], i < A_LOADS ? koff_a : koff_w, 0, 0);
+    };
+
+    // ---- fragment addressing: lane (frow, fhalf) feeds k = 64*kb + 32*fhalf .. +31 of its row, i.e.
+    // group f = 2*kb + fhalf of the row's block: 16 bytes among the pieces, 8 bytes among the tails
+    const int frow = lane & 31, fhalf = lane >> 5;
+    int moff[2], toff[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        moff[kb] = 64 * frow + 16 * ((2 * kb + fhalf) ^ ((frow >> 2) & 3));
+        toff[kb] = 2048 + 256 * (2 * kb + fhalf) + 8 * frow;
+    }
+    const int a_row = (wm * WM / 32) * BLOCK;
+    const int b_row = (BM / 32 + wn * WN / 32) * BLOCK;
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // ---- prologue: fill STAGES-1 stages
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < ksteps) issue_loads(s);
+    // at most (STAGES-2) later stages may still be in flight when stage 0 is needed
+    if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+
+    // Operand registers: six consecutive VGPRs per fragment (the builtin takes eight; the fp6 form of
+    // the instruction reads the first six).  The two LDS reads of a fragment land in them directly.
+    v8i pa[2][TM], pb[2][TN];
+#pragma unroll
+    for (int set = 0; set < 2; ++set) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) pa[set][i] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < TN; ++j) pb[set][j] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    // Byte offsets of the 8-byte tail reads, one opaque register each: reads whose addresses share a
+    // visible base get merged into paired reads, whose result could not land in two operand tuples
+    // without register copies.
+    int ta[2][TM], tb[2][TN];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) { ta[kb][i] = a_row + i * BLOCK + toff[kb]; asm volatile("" : "+v"(ta[kb][i])); }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { tb[kb][j] = b_row + j * BLOCK + toff[kb]; asm volatile("" : "+v"(tb[kb][j])); }
+    }
+    auto read_one = [&](v8i& dst, const uint8_t* main_ptr, const uint8_t* tail_ptr) {
+        const v4i m = *reinterpret_cast<const v4i*>(main_ptr);
+        const v2i t = *reinterpret_cast<const v2i*>(tail_ptr);
+        dst[0] = m[0]; dst[1] = m[1]; dst[2] = m[2]; dst[3] = m[3]; dst[4] = t[0]; dst[5] = t[1];
+    };
+    auto read_frags = [&](const uint8_t* st, int kb, int set) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) read_one(pa[set][i], st + a_row + i * BLOCK + moff[kb], st + ta[kb][i]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) read_one(pb[set][j], st + b_row + j * BLOCK + moff[kb], st + tb[kb][j]);
+    };
+    auto compute = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[set][i], pb[set][j], acc[i][j], 2, 2, 0, 0, 0, 0);
+    };
+    read_frags(lds, 0, 0);
+
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
+        // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
+        if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
+        // kb = 0: read kb = 1 of this stage ahead
+        read_frags(st, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
+        // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
+        if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+        if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+
+    // ---- epilogue: row and column constants through LDS (free now)
+    float4* lrow_par = reinterpret_cast<float4*>(lds);
+    float4* lcol_par = lrow_par + BM;
+    int* lcol_term = reinterpret_cast<int*>(lcol_par + BN);
+    for (int i = tid; i < BM; i += THREADS) {
+        int64_t m = m0 + i;
+        m = m < a.M ? m : a.M - 1;
+        const basq_tokmeta mt = a.meta[m];
+        // .w carries 30 * rowsum as an integer bit pattern
+        lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, __int_as_float(30 * mt.rowsum));
+    }
+    for (int i = tid; i < BN; i += THREADS) {
+        int n = n0 + i;
+        n = n < a.N ? n : a.N - 1;
+        lcol_par[i] = make_float4(bf16_to_f32(a.w_scale[n]), bf16_to_f32(a.w_zero[n]), a.w_sum[n],
+                                  a.out_bias ? a.out_bias[n] : 0.0f);
+        lcol_term[i] = 30 * a.w_codesum[n] - 225 * a.K;
+    }
+    __syncthreads();
+
+    const int col_in_tile = lane & 31, rgrp = lane >> 5;
+    float4 cp[TN];
+    int ct[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
+        ct[j] = lcol_term[wn * WN + j * 32 + col_in_tile];
+    }
+    // integer accumulator of the INT4 product from the exact fp32 sum of the shifted codes
+    auto int_acc = [&](float s, int row_term, int col_term) -> int {
+        return (__float2int_rn(4.0f * s) + row_term + col_term) >> 2;
+    };
+
+    const bool vec_ok = a.acc_out == nullptr && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
+    if (vec_ok) {
+        constexpr int PITCH = WN * 2 + 16;                      // bytes
+        constexpr int CH_PER_ROW = WN / 8;                      // 16-byte pieces per row
+        constexpr int PIECES = 32 * CH_PER_ROW / 64;            // per lane per 32-row block
+        constexpr int PARAM_BYTES = (BM + BN) * 16 + BN * 4;
+        uint8_t* patch = lds + PARAM_BYTES + wave * (32 * PITCH);
+        static_assert(PARAM_BYTES % 16 == 0 && PARAM_BYTES + WAVES * 32 * PITCH <= STAGES * STAGE_BYTES, "epilogue staging does not fit");
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
+                const float4 rp = lrow_par[wm * WM + i * 32 + rloc];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int av = int_acc(acc[i][j][r], __float_as_int(rp.w), ct[j]);
+                    const float t = (float)av - cp[j].y * rp.z;
+                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
+                    *reinterpret_cast<uint16_t*>(patch + rloc * PITCH + (j * 32 + col_in_tile) * 2) = f32_to_bf16(y);
+                }
+            }
+            // one wave's LDS operations complete in order: the reads below see the writes above
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < PIECES; ++q) {
+                const int id = q * 64 + lane;
+                const int rloc = id / CH_PER_ROW, ch = id % CH_PER_ROW;
+                const uint4 v = *reinterpret_cast<const uint4*>(patch + rloc * PITCH + ch * 16);
+                const int64_t m = m0 + wm * WM + i * 32 + rloc;
+                const int n = n0 + wn * WN + ch * 8;
+                if (m < a.M) {
+                    uint16_t* dst = a.Y + m * a.ldy + n;
+                    if (n + 8 <= a.N) {
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    } else {
+                        const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
+                                               (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) if (n + u < a.N) dst[u] = e[u];
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = wm * WM + i * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
+            const int64_t m = m0 + row;
+            if (m >= a.M) continue;
+            const float4 rp = lrow_par[row];
+            uint16_t* yrow = a.Y + m * a.ldy;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * WN + j * 32 + col_in_tile;
+                if (n < a.N) {
+                    const int av = int_acc(acc[i][j][r], __float_as_int(rp.w), ct[j]);
+                    const float t = (float)av - cp[j].y * rp.z;
+                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
+                    yrow[n] = f32_to_bf16(y);
+                    if (a.acc_out) a.acc_out[m * (int64_t)a.N + n] = av;
+                }
+            }
+        }
+    }
+#endif  // __HIP_DEVICE_COMPILE__
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, int MINOCC>
+int launch_fp6(const GemmArgs& a, hipStream_t s) {
+    const int64_t tm = (a.M + BM - 1) / BM;
+    const int64_t tn = ((int64_t)a.N + BN - 1) / BN;
+    if (tm * tn > 0x7FFFFFFFll) return fail(BASQ_EINVAL, "w4a4_gemm: problem too large for one launch");
+    hipLaunchKernelGGL((gemm_w4a4_fp6_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, MINOCC>), dim3((unsigned)(tm * tn)),
+                       dim3(WAVES_M * WAVES_N * 64), 0, s, a, (int)tm, (int)tn);
+    return check_hip(hipGetLastError(), "w4a4_gemm (fp6) launch");
+}
+
+double round_efficiency6(int64_t tiles, int64_t slots) {
+    const int64_t rounds = (tiles + slots - 1) / slots;
+    return (double)tiles / (double)(rounds * slots);
+}
+
+}  // namespace
+
+bool gemm_fp6_applicable(const GemmArgs& a) {
+    // buffer addressing: both operands must be smaller than 4 GiB
+    return a.Aq6 && a.Wq6 && a.w_codesum && a.K % 128 == 0 && a.M >= 1 &&
+           (int64_t)basq_fp6_bytes(a.M, a.K) < 0xFFFFFFFFll && (int64_t)basq_fp6_bytes(a.N, a.K) < 0xFFFFFFFFll;
+}
+
+int launch_gemm_fp6(const GemmArgs& a, hipStream_t s) {
+#ifdef GEMM_FP6_CFG
+    return launch_fp6<GEMM_FP6_CFG>(a, s);
+#else
+    auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * (((int64_t)a.N + bn - 1) / bn); };
+    const double s_big = 1.00 * round_efficiency6(tiles(256, 256), 256);
+    const double s_small = 0.85 * round_efficiency6(tiles(128, 128), 512);
+    if (s_big >= s_small) return launch_fp6<256, 256, 2, 4, 3, 2>(a, s);
+    return launch_fp6<128, 128, 2, 2, 3, 2>(a, s);
+#endif
+}
+
+}  // namespace basq

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_error_text(lib):
     assert B.basq_version() >= 100
-    rc = lib.basq_rotate_quant(None, 4, 100, 100, 64, None, None, 0.9, 0.9, 4, 0, None, None, None, None)
+    rc = lib.basq_rotate_quant(None, 4, 100, 100, 64, None, None, 0.9, 0.9, 4, 0, None, None, None, None, None)
     assert rc == B.BASQ_EINVAL and "multiple of 32" in B.basq_last_error()
 
 
@@ -62,13 +62,15 @@ FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fa
     (dict(Aq=None), B.BASQ_EINVAL),
     (dict(meta=None), B.BASQ_EINVAL),
     (dict(K=65536, ldx=65536, rot=65536), B.BASQ_EUNSUPPORTED),
+    (dict(K=1056, ldx=1056, rot=32, Aq6=FAKE), B.BASQ_EINVAL),        # fp6 form needs K % 128 == 0
+    (dict(Aq6=ctypes.c_void_p(0x1008)), B.BASQ_EINVAL),
 ])
 def test_rotate_quant_rejects_bad_arguments(lib, kw, code):
     a = dict(X=FAKE, M=4, K=1024, ldx=1024, rot=1024, bias=None, sa=None, clip_lo=0.9, clip_hi=0.9, bits=4,
-             group=0, Aq=FAKE, meta=FAKE, rot_out=None)
+             group=0, Aq=FAKE, meta=FAKE, rot_out=None, Aq6=None)
     a.update(kw)
     rc = lib.basq_rotate_quant(a["X"], a["M"], a["K"], a["ldx"], a["rot"], a["bias"], a["sa"], a["clip_lo"],
-                               a["clip_hi"], a["bits"], a["group"], a["Aq"], a["meta"], a["rot_out"], None)
+                               a["clip_hi"], a["bits"], a["group"], a["Aq"], a["meta"], a["rot_out"], a["Aq6"], None)
     assert rc == code, B.basq_last_error()
     assert B.basq_last_error() != ""
 
@@ -87,29 +89,49 @@ def test_rotate_quant_rejects_bad_arguments(lib, kw, code):
     (dict(Y=None), B.BASQ_EINVAL),
     (dict(Aq=ctypes.c_void_p(0x1004)), B.BASQ_EINVAL),
     (dict(Y=ctypes.c_void_p(0x1001)), B.BASQ_EINVAL),
+    (dict(Aq6=FAKE), B.BASQ_EINVAL),                                  # fp6 operands: all three or none
+    (dict(Aq6=FAKE, Wq6=FAKE), B.BASQ_EINVAL),
+    (dict(Wq6=FAKE, w_codesum=FAKE), B.BASQ_EINVAL),
+    (dict(K=1056, Aq6=FAKE, Wq6=FAKE, w_codesum=FAKE), B.BASQ_EINVAL),
+    (dict(Aq6=FAKE, Wq6=ctypes.c_void_p(0x1004), w_codesum=FAKE), B.BASQ_EINVAL),
 ])
 def test_gemm_rejects_bad_arguments(lib, kw, code):
     a = dict(Aq=FAKE, meta=FAKE, M=8, K=1024, Wq=FAKE, N=256, layout=0, w_scale=FAKE, w_zero=FAKE, w_sum=FAKE,
-             out_bias=None, Y=FAKE, ldy=256, acc=None)
+             out_bias=None, Y=FAKE, ldy=256, acc=None, Aq6=None, Wq6=None, w_codesum=None)
     a.update(kw)
     rc = lib.basq_w4a4_gemm(a["Aq"], a["meta"], a["M"], a["K"], a["Wq"], a["N"], a["layout"], a["w_scale"],
-                            a["w_zero"], a["w_sum"], a["out_bias"], a["Y"], a["ldy"], a["acc"], None)
+                            a["w_zero"], a["w_sum"], a["out_bias"], a["Y"], a["ldy"], a["acc"], a["Aq6"], a["Wq6"],
+                            a["w_codesum"], None)
     assert rc == code, B.basq_last_error()
 
 
 def test_fused_call_checks_workspace(lib):
     need = B.basq_workspace_bytes(64, 1024, 256)
     assert need >= 64 * 512 + 64 * 16 and need % 256 == 0
-    args = [FAKE, 64, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, FAKE, 256, 0, FAKE, FAKE, FAKE, None, FAKE, 256]
+    assert need >= 64 * 512 + 64 * 16 + B.basq_fp6_bytes(64, 1024)
+    args = [FAKE, 64, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, FAKE, 256, 0, FAKE, FAKE, FAKE, None, FAKE, 256,
+            None, None]
     assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2000), need - 1, None) == B.BASQ_EWORKSPACE
     assert "workspace too small" in B.basq_last_error()
     assert lib.basq_linear_fused(*args, None, need, None) == B.BASQ_EINVAL
     assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2010), need, None) == B.BASQ_EINVAL
+    half = args[:-2] + [FAKE, None]                                   # fp6 weights without their code sums
+    assert lib.basq_linear_fused(*half, ctypes.c_void_p(0x2000), need, None) == B.BASQ_EINVAL
+
+
+def test_fp6_form_sizes_and_argument_checks(lib):
+    assert B.basq_fp6_bytes(64, 1024) == 64 * 768
+    assert B.basq_fp6_bytes(33, 256) == 64 * 192                      # whole 32-row blocks
+    assert B.basq_fp6_bytes(5, 100) == 0 and B.basq_fp6_bytes(-1, 128) == 0
+    assert lib.basq_pack_fp6(FAKE, 8, 100, FAKE, None, None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(None, 8, 128, FAKE, None, None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(FAKE, 8, 128, ctypes.c_void_p(0x1008), None, None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(None, 0, 128, None, None, None) == 0
 
 
 def test_zero_tokens_is_valid_without_a_launch(lib):
-    assert lib.basq_rotate_quant(None, 0, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, None, None, None, None) == 0
-    assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None) == 0
+    assert lib.basq_rotate_quant(None, 0, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, None, None, None, None, None) == 0
+    assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None, None, None, None) == 0
 
 
 def test_offline_helpers_reject_bad_arguments(lib):
