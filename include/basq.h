@@ -104,25 +104,24 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
  *   out_bias   fp32 [N] c, or NULL (= 0)
  *   Y          out, bf16 [M, ldy], ldy >= N
  *   acc_out    out, optional debug dump of ACC, int32 [M, N]; NULL to skip
- *   Aq6, Wq6, w_codesum   optional, all three or none: both code matrices in the fp6 operand form and
- *              the per-channel code sums (basq_pack_fp6; Aq6 also straight from basq_rotate_quant).
- *              With them, and M > 16, the product runs on the f8f6f4 matrix-core path at twice the
- *              int8 rate; ACC and Y are bit-identical to the int8 path.  Needs K % 128 == 0.
+ *   Aq6, Wq6   optional, both or neither: the two code matrices in the fp6 operand form
+ *              (basq_pack_fp6; Aq6 also straight from basq_rotate_quant).  With them, and M > 16, the
+ *              product runs on the f8f6f4 matrix-core path at twice the int8 rate; ACC and Y are
+ *              bit-identical to the int8 path.  Needs K % 128 == 0.
  * Any M >= 0, N >= 1; small M (decode) takes a weight-streaming path, same results.
  */
 int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K,
                    const uint8_t* Wq, int32_t N, int32_t w_layout,
                    const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
                    void* Y, int64_t ldy, int32_t* acc_out,
-                   const uint8_t* Aq6, const uint8_t* Wq6, const int32_t* w_codesum, void* stream);
+                   const uint8_t* Aq6, const uint8_t* Wq6, void* stream);
 
 /*
  * The fp6 operand form of an INT4 code matrix (device-side repacking; offline for weights).
  * The matrix cores of this GPU multiply 6-bit floating-point operands (e2m3: sign, 2 exponent bits,
- * 3 mantissa bits) at twice their int8 rate.  Code q in 0..15 is stored as the e2m3 number q - 7.5,
- * which is exact; sum_k (qa-7.5)(qb-7.5) is exact in the fp32 accumulator for K <= 32768, and the
- * INT32 accumulator of the INT4 GEMM (Sec. 5.2) is recovered from it with the two code sums:
- *     sum_k qa*qb = S + 7.5*(sum_k qa + sum_k qb) - 56.25*K.
+ * 3 mantissa bits) at twice their int8 rate.  Code q in 0..15 is stored as the e2m3 number q/2, which
+ * is exact; S = sum_k (qa/2)(qb/2) is exact in the fp32 accumulator for K <= 32768, and the INT32
+ * accumulator of the INT4 GEMM (Sec. 5.2) is 4*S.
  *
  *   codes      device uint8 [rows, K/2], two codes per byte, low nibble first (as Aq and Wq)
  *   out6       out, device uint8, basq_fp6_bytes(rows, K) bytes, 16-byte aligned.  Blocks of 3072
@@ -131,11 +130,10 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
  *              128c + 32f .. +31) is a 24-byte little-endian string of 6-bit fields; its first 16 bytes
  *              sit at 64r + 16*(f ^ ((r>>2)&3)), its last 8 bytes at 2048 + 256f + 8r.  (The block is
  *              the image the GEMM keeps in LDS.)  Rows past the matrix in the last block stay unwritten.
- *   codesum    out, optional, device int32 [rows]: sum_k q[row, k]  (w_codesum of basq_w4a4_gemm)
  * K % 128 == 0.  basq_fp6_bytes returns ceil(rows/32)*32 * 3K/4 (0 for an unsupported K).
  */
 size_t basq_fp6_bytes(int64_t rows, int32_t K);
-int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, int32_t* codesum, void* stream);
+int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, void* stream);
 
 /* Bytes of workspace basq_linear_fused needs for this shape (activation codes, token records, and
  * the fp6 copy of the codes). */
@@ -144,15 +142,15 @@ size_t basq_workspace_bytes(int64_t M, int32_t K, int32_t N);
 /*
  * The whole layer in one call: basq_rotate_quant then basq_w4a4_gemm on `stream`, the codes and
  * token records living in `workspace` (256-byte aligned, >= basq_workspace_bytes(M, K, N), else
- * BASQ_EWORKSPACE).  Arguments as in the two calls above; with Wq6 and w_codesum (both or neither)
- * a prefill-sized M takes the fp6 matrix-core path.
+ * BASQ_EWORKSPACE).  Arguments as in the two calls above; with Wq6 a prefill-sized M takes the fp6
+ * matrix-core path.
  */
 int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
                       const float* bias, const float* act_scale,
                       float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
                       const uint8_t* Wq, int32_t N, int32_t w_layout,
                       const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
-                      void* Y, int64_t ldy, const uint8_t* Wq6, const int32_t* w_codesum,
+                      void* Y, int64_t ldy, const uint8_t* Wq6,
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- offline helpers (not on the timed path) --------------------------------------------- */

@@ -51,16 +51,16 @@ def load() -> ctypes.CDLL:
     lib.basq_rotate_quant.restype = c.c_int
     lib.basq_rotate_quant.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32, vp, vp, vp, vp, vp]
     lib.basq_w4a4_gemm.restype = c.c_int
-    lib.basq_w4a4_gemm.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.basq_w4a4_gemm.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.basq_fp6_bytes.restype = c.c_size_t
     lib.basq_fp6_bytes.argtypes = [i64, i32]
     lib.basq_pack_fp6.restype = c.c_int
-    lib.basq_pack_fp6.argtypes = [vp, i64, i32, vp, vp, vp]
+    lib.basq_pack_fp6.argtypes = [vp, i64, i32, vp, vp]
     lib.basq_workspace_bytes.restype = c.c_size_t
     lib.basq_workspace_bytes.argtypes = [i64, i32, i32]
     lib.basq_linear_fused.restype = c.c_int
     lib.basq_linear_fused.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32,
-                                      vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, c.c_size_t, vp]
+                                      vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, c.c_size_t, vp]
     lib.basq_quantize_weights.restype = c.c_int
     lib.basq_quantize_weights.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp]
     lib.basq_fused_bias.restype = c.c_int
@@ -124,31 +124,30 @@ def basq_rotate_quant(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
 def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor,
                    w_zero: torch.Tensor, w_sum: torch.Tensor, out_bias: Optional[torch.Tensor], Y: torch.Tensor,
                    acc_out: Optional[torch.Tensor] = None, *, Aq6: Optional[torch.Tensor] = None,
-                   Wq6: Optional[torch.Tensor] = None, w_codesum: Optional[torch.Tensor] = None,
+                   Wq6: Optional[torch.Tensor] = None,
                    w_layout: int = BASQ_W_CANONICAL, stream: Optional[torch.cuda.Stream] = None) -> None:
     M, KB = Aq.shape
     N = Wq.shape[0]
     _check(load().basq_w4a4_gemm(_p(Aq), _p(meta), M, KB * 2, _p(Wq), N, w_layout, _p(w_scale), _p(w_zero),
                                  _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _p(acc_out),
-                                 _p(Aq6), _p(Wq6), _p(w_codesum), _stream(stream)))
+                                 _p(Aq6), _p(Wq6), _stream(stream)))
 
 
 def basq_fp6_bytes(rows: int, K: int) -> int:
     return int(load().basq_fp6_bytes(rows, K))
 
 
-def basq_pack_fp6(codes: torch.Tensor, out6: torch.Tensor, codesum: Optional[torch.Tensor] = None, *,
-                  stream: Optional[torch.cuda.Stream] = None) -> None:
-    """codes uint8 [rows, K/2] -> out6 uint8 [rows, 3K/4] (fp6 operand form), codesum int32 [rows] (optional)."""
+def basq_pack_fp6(codes: torch.Tensor, out6: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """codes uint8 [rows, K/2] -> out6 uint8 [basq_fp6_bytes(rows, K)] (fp6 operand form)."""
     rows, KB = codes.shape
-    _check(load().basq_pack_fp6(_p(codes), rows, KB * 2, _p(out6), _p(codesum), _stream(stream)))
+    _check(load().basq_pack_fp6(_p(codes), rows, KB * 2, _p(out6), _stream(stream)))
 
 
 def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tensor],
                       act_scale: Optional[torch.Tensor], clip_lo: float, clip_hi: float, Wq: torch.Tensor,
                       w_scale: torch.Tensor, w_zero: torch.Tensor, w_sum: torch.Tensor,
                       out_bias: Optional[torch.Tensor], Y: torch.Tensor, workspace: torch.Tensor, *,
-                      Wq6: Optional[torch.Tensor] = None, w_codesum: Optional[torch.Tensor] = None,
+                      Wq6: Optional[torch.Tensor] = None,
                       bits: int = 4, group_size: int = 0, w_layout: int = BASQ_W_CANONICAL,
                       stream: Optional[torch.cuda.Stream] = None) -> None:
     M, K = X.shape
@@ -156,7 +155,7 @@ def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
     _check(load().basq_linear_fused(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
                                     clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout, _p(w_scale),
                                     _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
-                                    _p(Wq6), _p(w_codesum), _p(workspace),
+                                    _p(Wq6), _p(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
@@ -200,10 +199,9 @@ def alloc_activation_buffers(M: int, K: int, device="cuda") -> Tuple[torch.Tenso
             torch.empty((M, 4), dtype=torch.int32, device=device))
 
 
-def alloc_fp6_buffers(rows: int, K: int, device="cuda") -> Tuple[torch.Tensor, torch.Tensor]:
-    """(out6 uint8 [basq_fp6_bytes(rows, K)], codesum int32 [rows]) for basq_pack_fp6."""
-    return (torch.empty(basq_fp6_bytes(rows, K), dtype=torch.uint8, device=device),
-            torch.empty(rows, dtype=torch.int32, device=device))
+def alloc_fp6_buffer(rows: int, K: int, device="cuda") -> torch.Tensor:
+    """out6 uint8 [basq_fp6_bytes(rows, K)] for basq_pack_fp6 / the Aq6 output of basq_rotate_quant."""
+    return torch.empty(basq_fp6_bytes(rows, K), dtype=torch.uint8, device=device)
 
 
 def alloc_weight_buffers(N: int, K: int, device="cuda"):

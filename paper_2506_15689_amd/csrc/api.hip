@@ -79,11 +79,11 @@ int run_gemm(const GemmArgs& g, hipStream_t s) {
 }
 
 // the fp6 operand form is all-or-nothing on the GEMM side
-int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, const int32_t* w_codesum, bool need_a, int32_t K) {
-    const int given = (Wq6 != nullptr) + (w_codesum != nullptr) + (need_a ? (Aq6 != nullptr) : 0);
-    const int all = need_a ? 3 : 2;
+int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, bool need_a, int32_t K) {
+    const int given = (Wq6 != nullptr) + (need_a ? (Aq6 != nullptr) : 0);
+    const int all = need_a ? 2 : 1;
     if (given != 0 && given != all)
-        return fail(BASQ_EINVAL, "the fp6 operands (activations, weights, weight code sums) must be given together or not at all");
+        return fail(BASQ_EINVAL, "the fp6 operands (activations and weights) must be given together or not at all");
     if (given && K % 128 != 0) return fail(BASQ_EINVAL, "the fp6 operand form needs K %% 128 == 0 (got %d)", K);
     if (!aligned16(Aq6) || !aligned16(Wq6)) return fail(BASQ_EINVAL, "fp6 operands must be 16-byte aligned");
     return BASQ_OK;
@@ -93,7 +93,7 @@ int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, const int32_t* w_codesu
 int run_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     int rc = launch_rotate_quant(a, s);
     if (rc != BASQ_OK || !a.Aq6) return rc;
-    return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, nullptr, s);
+    return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -129,13 +129,13 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
 int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, const uint8_t* Wq, int32_t N,
                    int32_t w_layout, const void* w_scale, const void* w_zero, const float* w_sum,
                    const float* out_bias, void* Y, int64_t ldy, int32_t* acc_out,
-                   const uint8_t* Aq6, const uint8_t* Wq6, const int32_t* w_codesum, void* stream) {
+                   const uint8_t* Aq6, const uint8_t* Wq6, void* stream) {
     int rc = validate_gemm(Aq, meta, M, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
     if (rc != BASQ_OK) return rc;
-    rc = validate_fp6(Aq6, Wq6, w_codesum, true, K);
+    rc = validate_fp6(Aq6, Wq6, true, K);
     if (rc != BASQ_OK) return rc;
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, acc_out, Aq6, Wq6, w_codesum};
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, acc_out, Aq6, Wq6};
     return run_gemm(g, static_cast<hipStream_t>(stream));
 }
 
@@ -151,24 +151,24 @@ size_t basq_fp6_bytes(int64_t rows, int32_t K) {
     return (size_t)((rows + 31) / 32 * 32) * (size_t)(K / 4 * 3);      // whole 32-row blocks
 }
 
-int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, int32_t* codesum, void* stream) {
+int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, void* stream) {
     if (rows < 0) return fail(BASQ_EINVAL, "rows must be >= 0 (got %lld)", (long long)rows);
     if (K <= 0 || K % 128 != 0) return fail(BASQ_EINVAL, "the fp6 operand form needs K to be a positive multiple of 128 (got %d)", K);
     if (rows > 0 && (!codes || !out6)) return fail(BASQ_EINVAL, "codes or out6 is null");
     if (!aligned16(codes) || !aligned16(out6)) return fail(BASQ_EINVAL, "codes and out6 must be 16-byte aligned");
-    return launch_pack_fp6(codes, rows, K, out6, codesum, static_cast<hipStream_t>(stream));
+    return launch_pack_fp6(codes, rows, K, out6, static_cast<hipStream_t>(stream));
 }
 
 int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
                       const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
                       const uint8_t* Wq, int32_t N, int32_t w_layout, const void* w_scale, const void* w_zero,
                       const float* w_sum, const float* out_bias, void* Y, int64_t ldy,
-                      const uint8_t* Wq6, const int32_t* w_codesum, void* workspace,
+                      const uint8_t* Wq6, void* workspace,
                       size_t workspace_bytes, void* stream) {
     RotateQuantArgs a{};
     int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
     if (rc != BASQ_OK) return rc;
-    rc = validate_fp6(nullptr, Wq6, w_codesum, false, K);
+    rc = validate_fp6(nullptr, Wq6, false, K);
     if (rc != BASQ_OK) return rc;
     if (M == 0) {
         return validate_gemm(nullptr, nullptr, 0, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
@@ -195,7 +195,7 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     rc = run_rotate_quant(a, s);
     if (rc != BASQ_OK) return rc;
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, Aq6 ? w_codesum : nullptr};
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr};
     return run_gemm(g, s);
 }
 

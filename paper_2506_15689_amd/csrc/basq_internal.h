@@ -52,10 +52,9 @@ struct GemmArgs {
     uint16_t* Y;
     int64_t ldy;
     int32_t* acc_out;
-    // fp6 operand form of both matrices and the weight code sums; all three or none (gemm_w4a4_fp6.hip)
+    // fp6 operand form of both matrices; both or neither (gemm_w4a4_fp6.hip)
     const uint8_t* Aq6;
     const uint8_t* Wq6;
-    const int32_t* w_codesum;
 };
 int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 // direct-to-LDS kernel for K % 256 == 0 (gemm_w4a4_direct.hip)
@@ -65,8 +64,8 @@ int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
 // f8f6f4 MFMA kernel on the fp6 operand form, K % 128 == 0 (gemm_w4a4_fp6.hip)
 bool gemm_fp6_applicable(const GemmArgs& a);
 int launch_gemm_fp6(const GemmArgs& a, hipStream_t s);
-// INT4 codes [rows, K/2] -> fp6 operand form [rows, 3K/4] and optional per-row code sums (fp6_pack.hip)
-int launch_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, int32_t* codesum, hipStream_t s);
+// INT4 codes [rows, K/2] -> fp6 operand form (fp6_pack.hip)
+int launch_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, hipStream_t s);
 
 int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq,
                             uint16_t* w_scale, uint16_t* w_zero, float* w_sum, hipStream_t s);

@@ -1,10 +1,9 @@
 // INT4 codes -> the 6-bit floating-point operand form of the matrix core.
 //
-// A code q in 0..15 is stored as the e2m3 number q - 7.5 (sign, 2 exponent bits, 3 mantissa bits;
-// every half-integer up to 7.5 in magnitude is exact), so that the f8f6f4 MFMA, twice as fast as the
-// int8 one, accumulates sum_k (qa - 7.5)(qb - 7.5) exactly in fp32 (multiples of 1/4 below 2^21 for
-// K <= 32768).  The INT32 accumulator of the paper's INT4 GEMM (Sec. 5.2) follows from the code sums:
-//     sum_k qa*qb = S + 7.5*(sum_k qa + sum_k qb) - 56.25*K.
+// A code q in 0..15 is stored as the e2m3 number q/2 (sign, 2 exponent bits, 3 mantissa bits; every
+// multiple of 1/2 up to 7.5 is exact), so that the f8f6f4 MFMA, twice as fast as the int8 one, accumulates
+// S = sum_k (qa/2)(qb/2) exactly in fp32 (multiples of 1/4 below 2^21 for K <= 32768).  The INT32
+// accumulator of the paper's INT4 GEMM (Sec. 5.2) is 4*S.
 //
 // Layout: blocks of 3072 bytes, one per (chunk of 128 codes along K, block of 32 rows), chunk-major:
 // block (c, rb) sits at ((c * ceil(rows/32)) + rb) * 3072.  It is the image the GEMM wants in LDS, so a
@@ -19,17 +18,18 @@ namespace basq {
 
 namespace {
 
-// e2m3 encodings of 0.5, 1.5, ..., 7.5, one per byte
-constexpr uint64_t HALF_INT_CODES = 0x1F1D1B1916120C04ull;
-
+// e2m3 encoding of q/2: 0 -> 0; 1/2 is the subnormal 0.100b; from 1 on, exponent field 1 + floor(log2(q/2))
+// and the three bits below the leading one.  q >= 8 (values 4 .. 7.5, step 1/2) is 24 + (q - 8).
 __device__ __forceinline__ uint32_t fp6_of_code(uint32_t q) {
-    const uint32_t neg = q < 8u ? 1u : 0u;
-    const uint32_t h = neg ? 7u - q : q - 8u;
-    return (uint32_t)((HALF_INT_CODES >> (8u * h)) & 0x3Fu) | (neg << 5);
+    // one byte per code, 16 codes in two 64-bit words
+    constexpr uint64_t T0 = 0x161412100C080400ull;            // q = 0..7 : 0, 4, 8, 12, 16, 18, 20, 22
+    constexpr uint64_t T1 = 0x1F1E1D1C1B1A1918ull;            // q = 8..15: 24 .. 31
+    const uint64_t t = q < 8u ? T0 : T1;
+    return (uint32_t)(t >> (8u * (q & 7u))) & 0x3Fu;
 }
 
 __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict__ codes, int64_t rows, int32_t K,
-                                                        uint8_t* __restrict__ out6, int32_t* __restrict__ codesum) {
+                                                        uint8_t* __restrict__ out6) {
     // one wave per row: lane l converts groups l, l + 64, ...
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -39,7 +39,6 @@ __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict
     uint8_t* dst = out6 + (row >> 5) * 3072;                       // this row's block of chunk 0
     const int64_t chunk_pitch = ((rows + 31) >> 5) * 3072;
     const int swz = (r >> 2) & 3;
-    int sum = 0;
     for (int g = lane; g < K / 32; g += 64) {
         const uint4 in = *reinterpret_cast<const uint4*>(src + g * 16);
         const uint32_t w[4] = {in.x, in.y, in.z, in.w};
@@ -47,7 +46,6 @@ __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
             const uint32_t q = (w[e >> 3] >> (4 * (e & 7))) & 0xFu;
-            sum += (int)q;
             const uint32_t c = fp6_of_code(q);
             const int bit = 6 * e;
             o[bit >> 5] |= c << (bit & 31);
@@ -58,20 +56,15 @@ __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict
         *reinterpret_cast<uint4*>(blk + 64 * r + 16 * (f ^ swz)) = make_uint4(o[0], o[1], o[2], o[3]);
         *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2(o[4], o[5]);
     }
-    if (codesum) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-        if (lane == 0) codesum[row] = sum;
-    }
 }
 
 }  // namespace
 
-int launch_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, int32_t* codesum, hipStream_t s) {
+int launch_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, hipStream_t s) {
     if (rows == 0) return BASQ_OK;
     const int64_t blocks = (rows + 3) / 4;
     if (blocks > 0x7FFFFFFFll) return fail(BASQ_EINVAL, "pack_fp6: too many rows for one launch");
-    hipLaunchKernelGGL(pack_fp6_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, rows, K, out6, codesum);
+    hipLaunchKernelGGL(pack_fp6_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, rows, K, out6);
     return check_hip(hipGetLastError(), "pack_fp6 launch");
 }
 

@@ -1,11 +1,9 @@
 // Prefill INT4 x INT4 -> INT32 GEMM on the f8f6f4 matrix-core path (paper Sec. 5.2; Fig. 6; Eq. 14).
 //
-// Both operands arrive in the fp6 operand form of fp6_pack.hip: code q stored as the e2m3 number
-// q - 7.5.  v_mfma_f32_32x32x64_f8f6f4 with two fp6 operands runs at twice the int8 rate and its fp32
-// accumulator holds S = sum_k (qa - 7.5)(qb - 7.5) exactly (multiples of 1/4, |S| < 2^21 for K <= 32768).
-// The epilogue restores the integer accumulator of the INT4 product,
-//     ACC = (4S + 30*rowsum_m + 30*codesum_n - 225*K) / 4        (all integers, the division exact),
-// and de-quantises exactly as the int8 kernels do.
+// Both operands arrive in the fp6 operand form of fp6_pack.hip: code q stored as the e2m3 number q/2.
+// v_mfma_f32_32x32x64_f8f6f4 with two fp6 operands runs at twice the int8 rate and its fp32 accumulator
+// holds S = sum_k (qa/2)(qb/2) exactly (multiples of 1/4, S < 2^21 for K <= 32768).  The integer
+// accumulator of the INT4 product is ACC = 4*S; the epilogue de-quantises exactly as the int8 kernels do.
 //
 // Structure as in gemm_w4a4_direct.hip: direct-to-LDS buffer loads into a ring of stages, fragments
 // read one step ahead into two register sets, XCD-aware tile order.  A stage holds 128 codes per row.
@@ -51,8 +49,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
     constexpr int ROWS = BM + BN;
     constexpr int STAGE_BYTES = ROWS * CHUNK;
     constexpr int LOADS = STAGE_BYTES / (WAVES * 1024);       // direct loads (1 KB per wave) per thread per stage
-    constexpr int A_LOADS = BM * CHUNK / (WAVES * 1024);      // loads 0 .. A_LOADS-1 fetch activations
-    static_assert(STAGE_BYTES % (WAVES * 1024) == 0 && (BM * CHUNK) % (WAVES * 1024) == 0, "stage does not divide over the waves");
+    constexpr int A_PIECES = BM * CHUNK / 1024;               // 1 KB pieces 0 .. A_PIECES-1 of a stage are activations
+    static_assert(STAGE_BYTES % (WAVES * 1024) == 0, "stage does not divide over the waves");
     static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32-row blocks");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     static_assert(STAGES == 2 || STAGES == 3, "the wait counts below assume at most one stage in flight beyond the next");
@@ -96,7 +94,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         const int piece = i * WAVES + wave;
         int blk = piece / 3;
         const int part = piece % 3;
-        if (i < A_LOADS) {
+        if (piece < A_PIECES) {
             blk += (int)(m0 >> 5);
             blk = blk < rb_a ? blk : rb_a - 1;
         } else {
@@ -109,9 +107,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES + swave * 1024;
         const int koff_a = (int)((unsigned)ks * a_step), koff_w = (int)((unsigned)ks * w_step);   // unsigned 32-bit byte offsets
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(i < A_LOADS ? rsrc_a : rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16,
-                                                     voff[i], i < A_LOADS ? koff_a : koff_w, 0, 0);
+        for (int i = 0; i < LOADS; ++i) {
+            if (i * WAVES + swave < A_PIECES)                    // uniform over the wave
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, voff[i], koff_a, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, voff[i], koff_w, 0, 0);
+        }
     };
 
     // ---- fragment addressing: lane (frow, fhalf) feeds k = 64*kb + 32*fhalf .. +31 of its row, i.e.
@@ -204,42 +205,31 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
     // ---- epilogue: row and column constants through LDS (free now)
     float4* lrow_par = reinterpret_cast<float4*>(lds);
     float4* lcol_par = lrow_par + BM;
-    int* lcol_term = reinterpret_cast<int*>(lcol_par + BN);
     for (int i = tid; i < BM; i += THREADS) {
         int64_t m = m0 + i;
         m = m < a.M ? m : a.M - 1;
         const basq_tokmeta mt = a.meta[m];
-        // .w carries 30 * rowsum as an integer bit pattern
-        lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, __int_as_float(30 * mt.rowsum));
+        lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, 0.0f);
     }
     for (int i = tid; i < BN; i += THREADS) {
         int n = n0 + i;
         n = n < a.N ? n : a.N - 1;
         lcol_par[i] = make_float4(bf16_to_f32(a.w_scale[n]), bf16_to_f32(a.w_zero[n]), a.w_sum[n],
                                   a.out_bias ? a.out_bias[n] : 0.0f);
-        lcol_term[i] = 30 * a.w_codesum[n] - 225 * a.K;
     }
     __syncthreads();
 
     const int col_in_tile = lane & 31, rgrp = lane >> 5;
     float4 cp[TN];
-    int ct[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
-        ct[j] = lcol_term[wn * WN + j * 32 + col_in_tile];
-    }
-    // integer accumulator of the INT4 product from the exact fp32 sum of the shifted codes
-    auto int_acc = [&](float s, int row_term, int col_term) -> int {
-        return (__float2int_rn(4.0f * s) + row_term + col_term) >> 2;
-    };
+    for (int j = 0; j < TN; ++j) cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
 
     const bool vec_ok = a.acc_out == nullptr && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
     if (vec_ok) {
         constexpr int PITCH = WN * 2 + 16;                      // bytes
         constexpr int CH_PER_ROW = WN / 8;                      // 16-byte pieces per row
         constexpr int PIECES = 32 * CH_PER_ROW / 64;            // per lane per 32-row block
-        constexpr int PARAM_BYTES = (BM + BN) * 16 + BN * 4;
+        constexpr int PARAM_BYTES = (BM + BN) * 16;
         uint8_t* patch = lds + PARAM_BYTES + wave * (32 * PITCH);
         static_assert(PARAM_BYTES % 16 == 0 && PARAM_BYTES + WAVES * 32 * PITCH <= STAGES * STAGE_BYTES, "epilogue staging does not fit");
 #pragma unroll
@@ -250,8 +240,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
                 const float4 rp = lrow_par[wm * WM + i * 32 + rloc];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int av = int_acc(acc[i][j][r], __float_as_int(rp.w), ct[j]);
-                    const float t = (float)av - cp[j].y * rp.z;
+                    const float t = 4.0f * acc[i][j][r] - cp[j].y * rp.z;      // 4*S is the integer accumulator, exactly
                     const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
                     *reinterpret_cast<uint16_t*>(patch + rloc * PITCH + (j * 32 + col_in_tile) * 2) = f32_to_bf16(y);
                 }
@@ -294,7 +283,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WN + j * 32 + col_in_tile;
                 if (n < a.N) {
-                    const int av = int_acc(acc[i][j][r], __float_as_int(rp.w), ct[j]);
+                    const int av = __float2int_rn(4.0f * acc[i][j][r]);
                     const float t = (float)av - cp[j].y * rp.z;
                     const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
                     yrow[n] = f32_to_bf16(y);
@@ -325,7 +314,7 @@ double round_efficiency6(int64_t tiles, int64_t slots) {
 
 bool gemm_fp6_applicable(const GemmArgs& a) {
     // buffer addressing: both operands must be smaller than 4 GiB
-    return a.Aq6 && a.Wq6 && a.w_codesum && a.K % 128 == 0 && a.M >= 1 &&
+    return a.Aq6 && a.Wq6 && a.K % 128 == 0 && a.M >= 1 &&
            (int64_t)basq_fp6_bytes(a.M, a.K) < 0xFFFFFFFFll && (int64_t)basq_fp6_bytes(a.N, a.K) < 0xFFFFFFFFll;
 }
 

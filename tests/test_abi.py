@@ -89,19 +89,18 @@ def test_rotate_quant_rejects_bad_arguments(lib, kw, code):
     (dict(Y=None), B.BASQ_EINVAL),
     (dict(Aq=ctypes.c_void_p(0x1004)), B.BASQ_EINVAL),
     (dict(Y=ctypes.c_void_p(0x1001)), B.BASQ_EINVAL),
-    (dict(Aq6=FAKE), B.BASQ_EINVAL),                                  # fp6 operands: all three or none
-    (dict(Aq6=FAKE, Wq6=FAKE), B.BASQ_EINVAL),
-    (dict(Wq6=FAKE, w_codesum=FAKE), B.BASQ_EINVAL),
-    (dict(K=1056, Aq6=FAKE, Wq6=FAKE, w_codesum=FAKE), B.BASQ_EINVAL),
-    (dict(Aq6=FAKE, Wq6=ctypes.c_void_p(0x1004), w_codesum=FAKE), B.BASQ_EINVAL),
+    (dict(Aq6=FAKE), B.BASQ_EINVAL),                                  # fp6 operands: both or neither
+    (dict(Wq6=FAKE), B.BASQ_EINVAL),
+    (dict(K=1056, Aq6=FAKE, Wq6=FAKE), B.BASQ_EINVAL),
+    (dict(Aq6=FAKE, Wq6=ctypes.c_void_p(0x1004)), B.BASQ_EINVAL),
 ])
 def test_gemm_rejects_bad_arguments(lib, kw, code):
     a = dict(Aq=FAKE, meta=FAKE, M=8, K=1024, Wq=FAKE, N=256, layout=0, w_scale=FAKE, w_zero=FAKE, w_sum=FAKE,
-             out_bias=None, Y=FAKE, ldy=256, acc=None, Aq6=None, Wq6=None, w_codesum=None)
+             out_bias=None, Y=FAKE, ldy=256, acc=None, Aq6=None, Wq6=None)
     a.update(kw)
     rc = lib.basq_w4a4_gemm(a["Aq"], a["meta"], a["M"], a["K"], a["Wq"], a["N"], a["layout"], a["w_scale"],
                             a["w_zero"], a["w_sum"], a["out_bias"], a["Y"], a["ldy"], a["acc"], a["Aq6"], a["Wq6"],
-                            a["w_codesum"], None)
+                            None)
     assert rc == code, B.basq_last_error()
 
 
@@ -110,28 +109,30 @@ def test_fused_call_checks_workspace(lib):
     assert need >= 64 * 512 + 64 * 16 and need % 256 == 0
     assert need >= 64 * 512 + 64 * 16 + B.basq_fp6_bytes(64, 1024)
     args = [FAKE, 64, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, FAKE, 256, 0, FAKE, FAKE, FAKE, None, FAKE, 256,
-            None, None]
+            None]
     assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2000), need - 1, None) == B.BASQ_EWORKSPACE
     assert "workspace too small" in B.basq_last_error()
     assert lib.basq_linear_fused(*args, None, need, None) == B.BASQ_EINVAL
     assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2010), need, None) == B.BASQ_EINVAL
-    half = args[:-2] + [FAKE, None]                                   # fp6 weights without their code sums
-    assert lib.basq_linear_fused(*half, ctypes.c_void_p(0x2000), need, None) == B.BASQ_EINVAL
+    odd = list(args)
+    odd[2] = odd[3] = odd[4] = 1056                                   # fp6 weights need K % 128 == 0
+    odd[-1] = FAKE
+    assert lib.basq_linear_fused(*odd, ctypes.c_void_p(0x2000), 1 << 20, None) == B.BASQ_EINVAL
 
 
 def test_fp6_form_sizes_and_argument_checks(lib):
     assert B.basq_fp6_bytes(64, 1024) == 64 * 768
     assert B.basq_fp6_bytes(33, 256) == 64 * 192                      # whole 32-row blocks
     assert B.basq_fp6_bytes(5, 100) == 0 and B.basq_fp6_bytes(-1, 128) == 0
-    assert lib.basq_pack_fp6(FAKE, 8, 100, FAKE, None, None) == B.BASQ_EINVAL
-    assert lib.basq_pack_fp6(None, 8, 128, FAKE, None, None) == B.BASQ_EINVAL
-    assert lib.basq_pack_fp6(FAKE, 8, 128, ctypes.c_void_p(0x1008), None, None) == B.BASQ_EINVAL
-    assert lib.basq_pack_fp6(None, 0, 128, None, None, None) == 0
+    assert lib.basq_pack_fp6(FAKE, 8, 100, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(None, 8, 128, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(FAKE, 8, 128, ctypes.c_void_p(0x1008), None) == B.BASQ_EINVAL
+    assert lib.basq_pack_fp6(None, 0, 128, None, None) == 0
 
 
 def test_zero_tokens_is_valid_without_a_launch(lib):
     assert lib.basq_rotate_quant(None, 0, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, None, None, None, None, None) == 0
-    assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None, None, None, None) == 0
+    assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None, None, None) == 0
 
 
 def test_offline_helpers_reject_bad_arguments(lib):
