@@ -115,7 +115,7 @@ def test_fused_call_checks_workspace(lib):
     assert lib.basq_linear_fused(*args, None, need, None) == B.BASQ_EINVAL
     assert lib.basq_linear_fused(*args, ctypes.c_void_p(0x2010), need, None) == B.BASQ_EINVAL
     odd = list(args)
-    odd[2] = odd[3] = odd[4] = 1056                                   # fp6 weights need K % 128 == 0
+    odd[2] = odd[3] = 1056; odd[4] = 32                                     # fp6 weights need K % 128 == 0
     odd[-1] = FAKE
     assert lib.basq_linear_fused(*odd, ctypes.c_void_p(0x2000), 1 << 20, None) == B.BASQ_EINVAL
 
