@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
 
 # HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
 # under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
@@ -51,6 +52,9 @@ def parse_args():
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy three times (scales the HBM byte counters of a profiler run)")
     p.add_argument("--no-bias", action="store_true", help="run the kernels without the channel bias (experiments)")
+    p.add_argument("--matrix-path", default="fp6", choices=["fp6", "int8"],
+                   help="prefill GEMM on the f8f6f4 matrix-core path (codes repacked as exact fp6 values; default) "
+                        "or on the int8 path; decode-sized M always streams the INT4 weights")
     p.add_argument("--only", default="", choices=["", "rotate_quant"],
                    help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
     return p.parse_args()
@@ -122,6 +126,11 @@ def main():
     B.basq_calibrate_bias(Xc, cfg.rot_size, None, bias, cal_ws)
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
+    use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > 16
+    Wq6 = None
+    if use_fp6:                                # offline: the weights once more in the fp6 operand form
+        Wq6 = B.alloc_fp6_buffer(N, K, dev)
+        B.basq_pack_fp6(Wq, Wq6)
     torch.cuda.synchronize()
     del W, cal_ws, Xc
     if args.no_bias:
@@ -129,7 +138,7 @@ def main():
 
     # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
     rq_only = args.only == "rotate_quant"
-    per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2)
+    per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2) + (M * K * 3 // 4 if use_fp6 else 0)
     nsets = args.sets if args.sets > 0 else max(2, min(32, -(-(640 << 20) // per_set)))
     X0 = lay.X.to(dev)
     sets = []
@@ -137,25 +146,30 @@ def main():
         Xi = X0 if i == 0 else torch.roll(X0, shifts=i, dims=0).contiguous()
         Aq, meta = B.alloc_activation_buffers(M, K, dev)
         Y = None if rq_only else torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-        sets.append((Xi, Aq, meta, Y))
+        Aq6 = B.alloc_fp6_buffer(M, K, dev) if use_fp6 else None
+        sets.append((Xi, Aq, meta, Y, Aq6))
     workspace = torch.empty(max(256, B.basq_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
 
     def rotate_quant(i):
-        Xi, Aq, meta, _ = sets[i % nsets]
-        B.basq_rotate_quant(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, stream=stream)
+        Xi, Aq, meta, _, Aq6 = sets[i % nsets]
+        B.basq_rotate_quant(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, Aq6=Aq6, stream=stream)
 
     def gemm(i):
-        _, Aq, meta, Y = sets[i % nsets]
+        _, Aq, meta, Y, Aq6 = sets[i % nsets]
+        B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y, None, Aq6=Aq6, Wq6=Wq6, stream=stream)
+
+    def gemm_int8(i):
+        _, Aq, meta, Y, _ = sets[i % nsets]
         B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y, None, stream=stream)
 
     def step(i):
         """One pass of the whole hot path: the single fused entry point."""
-        Xi, _, _, Y = sets[i % nsets]
+        Xi, _, _, Y, _ = sets[i % nsets]
         B.basq_linear_fused(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Wq, w_scale, w_zero, w_sum, out_bias,
-                            Y, workspace, stream=stream)
+                            Y, workspace, Wq6=Wq6, stream=stream)
 
     def timed(fn, count):
         """`count` back-to-back calls bracketed by two events on the launch stream; ms per call."""
@@ -186,6 +200,7 @@ def main():
     _, ms_step = timed(whole, args.steps)
     rq_ms, _ = timed(rotate_quant, args.steps)
     gemm_ms = float("nan") if rq_only else timed(gemm, args.steps)[0]
+    gemm_int8_ms = timed(gemm_int8, args.steps)[0] if use_fp6 and not rq_only else None
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
@@ -223,6 +238,14 @@ def main():
         ms, _ = timed(mfma_once, 3)
         ceilings["int8_mfma_TOPS"] = 512 * 4 * 8 * iters * 65536.0 / (ms * 1e-3) / 1e12
         del cout
+        fout = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+
+        def mfma6_once(i):
+            B.basq_diag_mfma_f6(fout, 512, iters, stream=stream)
+        mfma6_once(0)
+        ms, _ = timed(mfma6_once, 3)
+        ceilings["fp6_mfma_TOPS"] = 512 * 4 * 8 * iters * 131072.0 / (ms * 1e-3) / 1e12
+        del fout
 
     rq_bytes = algorithmic_bytes_rotate_quant(M, K)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N)
@@ -237,9 +260,18 @@ def main():
                 "algorithmic_bytes": gemm_bytes, "avg_kernel_ms": gemm_ms}
     else:
         ach = ops / (gemm_ms * 1e-3) / 1e12
-        roof = {"kernel": "gemm_w4a4_direct_kernel", "bound": "mfma", "achieved": ach, "peak": INT8_PEAK_TOPS,
-                "unit": "TOP/s", "frac": ach / INT8_PEAK_TOPS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
-                "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
+        peak = FP6_PEAK_TOPS if use_fp6 else INT8_PEAK_TOPS
+        tkey = "gemm_fp6" if use_fp6 else "gemm"
+        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else "gemm_w4a4_direct_kernel", "bound": "mfma",
+                "achieved": ach, "peak": peak, "unit": "TOP/s", "frac": ach / peak,
+                "traffic": MEASURED_TRAFFIC.get((args.config, tkey)), "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
+        if use_fp6:
+            # the same product on the int8 matrix-core path (bit-identical output), for comparison
+            ach8 = ops / (gemm_int8_ms * 1e-3) / 1e12
+            roof["frac_of_int8_peak"] = ach / INT8_PEAK_TOPS
+            roof["int8_path"] = {"kernel": "gemm_w4a4_direct_kernel", "achieved": ach8, "peak": INT8_PEAK_TOPS,
+                                 "frac": ach8 / INT8_PEAK_TOPS, "avg_kernel_ms": gemm_int8_ms,
+                                 "traffic": MEASURED_TRAFFIC.get((args.config, "gemm"))}
     roof_rq = {"kernel": "rotate_quant", "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                "frac": rq_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "rotate_quant")),
                "algorithmic_bytes": rq_bytes, "avg_kernel_ms": rq_ms}
@@ -248,8 +280,11 @@ def main():
         roof_rq["measured_ceiling"] = ceilings["hbm_stream_GBps"]
         roof_rq["frac_of_measured_ceiling"] = rq_gbs / ceilings["hbm_stream_GBps"]
         if roof is not None and roof["bound"] == "mfma":
-            roof["measured_ceiling"] = ceilings["int8_mfma_TOPS"]
-            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["int8_mfma_TOPS"]
+            ckey = "fp6_mfma_TOPS" if use_fp6 else "int8_mfma_TOPS"
+            roof["measured_ceiling"] = ceilings[ckey]
+            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings[ckey]
+            if use_fp6:
+                roof["int8_path"]["measured_ceiling"] = ceilings["int8_mfma_TOPS"]
         elif roof is not None:
             roof["measured_ceiling"] = ceilings["hbm_stream_GBps"]
             roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["hbm_stream_GBps"]
@@ -258,10 +293,12 @@ def main():
         "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
         "value": rq_gbs if rq_only else value, "unit": "GB/s" if rq_only else "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4 x int4 -> int32 (int8 MFMA); rotation and quantiser in f32; bf16 in/out",
+        "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if use_fp6 and not rq_only
+                  else "int4 x int4 -> int32 (int8 MFMA)") + "; rotation and quantiser in f32; bf16 in/out",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": cfg.rot_size,
-                   "clip": cfg.clip, "buffer_sets": nsets},
+                   "clip": cfg.clip, "buffer_sets": nsets,
+                   "matrix_path": "fp6" if use_fp6 else ("int8" if M > 16 else "int4 weight streaming")},
         "rotate_quant_GBps": rq_gbs,
         "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,

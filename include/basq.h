@@ -204,6 +204,13 @@ int basq_diag_stream(const void* src, void* dst, void* meta, int64_t tokens, int
  */
 int basq_diag_mfma_i8(int32_t* out, int32_t blocks, int32_t iters, void* stream);
 
+/*
+ * The same loop on the f8f6f4 matrix-core path the prefill GEMM uses by default: each wave issues
+ * 8*iters v_mfma_f32_32x32x64_f8f6f4 with fp6 (e2m3) operands in the value range of the 4-bit codes;
+ * out receives blocks*256 fp32 checksums.  Executes blocks*4*8*iters*131072 operations.
+ */
+int basq_diag_mfma_f6(float* out, int32_t blocks, int32_t iters, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

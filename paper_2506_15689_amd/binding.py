@@ -21,7 +21,7 @@ BASQ_W_CANONICAL = 0
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
            "basq_fp6_bytes", "basq_pack_fp6", "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
-           "basq_hadamard28", "basq_diag_stream", "basq_diag_mfma_i8"]
+           "basq_hadamard28", "basq_diag_stream", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
 class BasqError(RuntimeError):
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.basq_diag_stream.argtypes = [vp, vp, vp, i64, i32, vp]
     lib.basq_diag_mfma_i8.restype = c.c_int
     lib.basq_diag_mfma_i8.argtypes = [vp, i32, i32, vp]
+    lib.basq_diag_mfma_f6.restype = c.c_int
+    lib.basq_diag_mfma_f6.argtypes = [vp, i32, i32, vp]
     _lib = lib
     return lib
 
@@ -189,6 +191,10 @@ def basq_diag_stream(src: torch.Tensor, dst: torch.Tensor, meta: torch.Tensor, t
 
 def basq_diag_mfma_i8(out: torch.Tensor, blocks: int, iters: int, *, stream: Optional[torch.cuda.Stream] = None) -> None:
     _check(load().basq_diag_mfma_i8(_p(out), blocks, iters, _stream(stream)))
+
+
+def basq_diag_mfma_f6(out: torch.Tensor, blocks: int, iters: int, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    _check(load().basq_diag_mfma_f6(_p(out), blocks, iters, _stream(stream)))
 
 
 # ---- allocation helpers (device memory only; no arithmetic) ----------------------------------

@@ -89,13 +89,6 @@ int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, bool need_a, int32_t K)
     return BASQ_OK;
 }
 
-// rotate + quantise, then the fp6 copy of the codes when asked for
-int run_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
-    int rc = launch_rotate_quant(a, s);
-    if (rc != BASQ_OK || !a.Aq6) return rc;
-    return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);
-}
-
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
@@ -123,7 +116,7 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
     a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
     a.Aq = Aq; a.meta = meta; a.rot_out = rot_out; a.Aq6 = Aq6;
-    return run_rotate_quant(a, static_cast<hipStream_t>(stream));
+    return launch_rotate_quant(a, static_cast<hipStream_t>(stream));
 }
 
 int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, const uint8_t* Wq, int32_t N,
@@ -192,7 +185,7 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
         Aq6 = reinterpret_cast<uint8_t*>(meta) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
     a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = run_rotate_quant(a, s);
+    rc = launch_rotate_quant(a, s);
     if (rc != BASQ_OK) return rc;
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
                w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr};

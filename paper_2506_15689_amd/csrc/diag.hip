@@ -3,6 +3,7 @@
 //   basq_diag_stream   a pure streaming kernel with the rotate+quant kernel's access pattern
 //                      (one wave per token, 2K bytes in, K/2 + 16 bytes out, non-temporal)
 //   basq_diag_mfma_i8  a register-resident v_mfma_i32_32x32x32_i8 loop, 4-bit valued operands
+//   basq_diag_mfma_f6  the same with v_mfma_f32_32x32x64_f8f6f4 on fp6 (e2m3) operands that encode 4-bit codes
 // Neither computes anything of the method.
 #include "basq_internal.h"
 
@@ -58,6 +59,43 @@ __global__ __launch_bounds__(256) void diag_mfma_kernel(int* out, int iters) {
     out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// six-bit fields of a dword pattern forced into the range of the codes' encodings (0..31: the e2m3 values
+// 0 .. 7.5 that stand for q/2); field boundaries do not matter for a throughput loop, only realistic bits
+__device__ __forceinline__ int fp6_bits(int x) { return x & 0x7DF7DF7D; }
+
+__global__ __launch_bounds__(256) void diag_mfma_f6_kernel(float* out, int iters) {
+    v16f acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    const int l = threadIdx.x;
+    v8i a[2], b[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            a[t][d] = d < 6 ? fp6_bits((l + 3 * t + 1) * (0x01030507 + 0x00020406 * d)) : 0;
+            b[t][d] = d < 6 ? fp6_bits((l + 5 * t + 2) * (0x0B0D1113 + 0x00040208 * d)) : 0;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 1], b[(i >> 1) & 1], acc[i], 2, 2, 0, 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[(i + 1) & 1], b[i & 1], acc[i], 2, 2, 0, 0, 0, 0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 }  // namespace basq
 
@@ -79,6 +117,12 @@ int basq_diag_mfma_i8(int32_t* out, int32_t blocks, int32_t iters, void* stream)
     if (!out || blocks < 1 || iters < 1) return fail(BASQ_EINVAL, "diag_mfma_i8: bad argument");
     hipLaunchKernelGGL(diag_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
     return check_hip(hipGetLastError(), "diag_mfma_i8 launch");
+}
+
+int basq_diag_mfma_f6(float* out, int32_t blocks, int32_t iters, void* stream) {
+    if (!out || blocks < 1 || iters < 1) return fail(BASQ_EINVAL, "diag_mfma_f6: bad argument");
+    hipLaunchKernelGGL(diag_mfma_f6_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
+    return check_hip(hipGetLastError(), "diag_mfma_f6 launch");
 }
 
 }  // extern "C"

@@ -187,10 +187,22 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_generic_kernel(Rotate
 
 }  // namespace
 
+namespace {
+int launch_rotate_quant_generic(const RotateQuantArgs& a, hipStream_t s);
+}
+
 int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     if (a.M == 0) return BASQ_OK;
+    // the two specialised kernels write the fp6 copy of the codes themselves
     if (rotate_quant_pow2_applicable(a)) return launch_rotate_quant_pow2(a, s);
     if (rotate_quant_k28_applicable(a)) return launch_rotate_quant_k28(a, s);
+    const int rc = launch_rotate_quant_generic(a, s);
+    if (rc != BASQ_OK || !a.Aq6 || !a.Aq) return rc;
+    return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);
+}
+
+namespace {
+int launch_rotate_quant_generic(const RotateQuantArgs& a, hipStream_t s) {
     int log2p = 0;
     while ((1 << log2p) < a.pow2) ++log2p;
     H28Masks masks{};
@@ -215,5 +227,7 @@ int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(rotate_quant_generic_kernel, dim3((unsigned)a.M), dim3(RQ_THREADS), lds, s, a, norm, log2p, masks);
     return check_hip(hipGetLastError(), "rotate_quant launch");
 }
+
+}  // namespace
 
 }  // namespace basq

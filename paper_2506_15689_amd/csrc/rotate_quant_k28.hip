@@ -22,6 +22,8 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v6i __attribute__((ext_vector_type(6)));
 
 constexpr int K28 = 14336;
 // Workgroups of four waves (two tokens), two per compute unit, while one 64 KB vector (b^c or s^a) is
@@ -123,8 +125,13 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         }
     };
 
+    // Workgroups g, g+8, ... share an XCD; renumbered so that an XCD owns a contiguous range, 32
+    // consecutive tokens (one block of the fp6 output) meet in one L2 and their pieces merge there.
+    int vblock = blockIdx.x;
+    if ((gridDim.x & 127) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int64_t rb6 = (a.M + 31) >> 5;                    // 32-row blocks per chunk of the fp6 output
     const int tokens_per_round = gridDim.x * (K28_WAVES / 2);
-    const int64_t m_first = (int64_t)blockIdx.x * (K28_WAVES / 2);
+    const int64_t m_first = (int64_t)vblock * (K28_WAVES / 2);
     v4u R[4][8];
     {
         const int64_t m = m_first + tok_in_blk;
@@ -294,6 +301,25 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                     sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
                 }
                 words[jb][r] = ev | (od << 4);
+            }
+            if (a.Aq6 && row_valid && tok_valid) {
+                // The 32 codes of group jb once more, as e2m3 numbers q/2 (the packed conversion divides by
+                // its scale operand and interleaves even and odd codes).  A lane's 128 channels are one
+                // 128-code chunk of the fp6 layout: chunk 4*i' + g, group jb.
+                v16f qe, qo;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        qe[4 * r + p] = (float)((words[jb][r] >> (8 * p)) & 0xFu);
+                        qo[4 * r + p] = (float)((words[jb][r] >> (8 * p + 4)) & 0xFu);
+                    }
+                const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 2.0f);
+                const int rr = (int)(m & 31);
+                uint8_t* blk = a.Aq6 + ((int64_t)(4 * ip + g) * rb6 + (m >> 5)) * 3072;
+                *reinterpret_cast<uint4*>(blk + 64 * rr + 16 * (jb ^ ((rr >> 2) & 3))) =
+                    make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
+                *reinterpret_cast<uint2*>(blk + 2048 + 256 * jb + 8 * rr) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
             }
         }
         // A lane holds 64 consecutive output bytes as four 16-byte pieces.  Transposing the pieces over

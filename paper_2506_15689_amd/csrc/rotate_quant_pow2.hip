@@ -25,6 +25,8 @@ namespace basq {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v6i __attribute__((ext_vector_type(6)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef short v8s __attribute__((ext_vector_type(8)));
 
@@ -137,8 +139,14 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     // LDS read base: lane bits (0..5) = (e5..e10)
     const int rbase = ((lane & 15) << 1) | ((lane & 3) << 5) | (((lane >> 4) & 3) << 9);
 
-    const int wave_id = blockIdx.x * P2_WAVES + wave;
+    // Workgroups g, g+8, g+16, ... run on one XCD.  Renumbering them so that an XCD owns a contiguous
+    // range makes 32 consecutive tokens (one block of the fp6 output) meet in one L2, where their 8- and
+    // 16-byte pieces merge into whole lines before they are written back.
+    int vblock = blockIdx.x;
+    if ((gridDim.x & 63) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int wave_id = vblock * P2_WAVES + wave;
     const int wave_stride = gridDim.x * P2_WAVES;
+    const int64_t rb6 = (a.M + 31) >> 5;                       // 32-row blocks per chunk of the fp6 output
 
     uint4 raw[NC];
     auto load_token = [&](int64_t m) {
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
         for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                uint32_t words[4];
+                uint32_t words[4], evs[4], ods[4];
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     uint32_t ev = 0, od = 0;
@@ -292,9 +300,29 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                     sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
                     sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
                     words[w] = ev | (od << 4);
+                    evs[w] = ev; ods[w] = od;
                 }
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
+                if (a.Aq6) {
+                    // the same 32 codes as e2m3 numbers q/2: the packed conversion divides by its scale
+                    // operand and interleaves its two sources (even and odd codes)
+                    v16f qe, qo;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            qe[4 * w + j] = (float)((evs[w] >> (8 * j)) & 0xFFu);
+                            qo[4 * w + j] = (float)((ods[w] >> (8 * j)) & 0xFFu);
+                        }
+                    const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 2.0f);
+                    // group 128*hf + 64*b + lane of the token: chunk (group / 4), position (group % 4)
+                    const int g = 128 * hf + 64 * b + lane, f = g & 3, r = (int)(m & 31);
+                    uint8_t* blk = a.Aq6 + ((int64_t)(g >> 2) * rb6 + (m >> 5)) * 3072;
+                    *reinterpret_cast<uint4*>(blk + 64 * r + 16 * (f ^ ((r >> 2) & 3))) =
+                        make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
+                    *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
+                }
             }
         sum = wave_sum_i(sum);
         if (lane == 0) {
