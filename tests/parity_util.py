@@ -93,6 +93,12 @@ class GpuResult:
     acc: np.ndarray        # int32 [M, N]
     y_bits: np.ndarray     # uint16 [M, N]
     y_fused_bits: np.ndarray
+    # the same layer on the fp6 matrix-core path (None when K % 128 != 0)
+    a6: Optional[np.ndarray] = None          # fp6 operand form of the activation codes, as written by rotate_quant
+    w6: Optional[np.ndarray] = None          # ... of the weight codes, as written by pack_fp6
+    acc6: Optional[np.ndarray] = None
+    y6_bits: Optional[np.ndarray] = None
+    y6_fused_bits: Optional[np.ndarray] = None
 
 
 def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
@@ -110,9 +116,58 @@ def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
                         d.w_zero, d.w_sum, d.out_bias, Yf, ws)
     torch.cuda.synchronize()
     meta_h = meta.cpu().numpy()
-    return GpuResult(rot.cpu().numpy(), oracle.unpack_codes(Aq.cpu().numpy()),
-                     meta_h[:, 0].copy().view(np.float32), meta_h[:, 1].copy().view(np.float32),
-                     meta_h[:, 2].copy(), acc.cpu().numpy(), si.bf16_bits(Y.cpu()), si.bf16_bits(Yf.cpu()))
+    res = GpuResult(rot.cpu().numpy(), oracle.unpack_codes(Aq.cpu().numpy()),
+                    meta_h[:, 0].copy().view(np.float32), meta_h[:, 1].copy().view(np.float32),
+                    meta_h[:, 2].copy(), acc.cpu().numpy(), si.bf16_bits(Y.cpu()), si.bf16_bits(Yf.cpu()))
+    if K % 128 == 0 and M > 0:
+        # second pass with the fp6 operands: activations straight from rotate_quant, weights repacked
+        Aq2, meta2 = B.alloc_activation_buffers(M, K, dev)
+        A6 = B.alloc_fp6_buffer(M, K, dev).zero_()
+        W6 = B.alloc_fp6_buffer(N, K, dev).zero_()
+        Y6 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+        Y6f = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+        acc6 = torch.full((M, N), -1, dtype=torch.int32, device=dev)
+        B.basq_pack_fp6(d.Wq, W6)
+        B.basq_rotate_quant(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, Aq2, meta2, None, Aq6=A6)
+        B.basq_w4a4_gemm(Aq2, meta2, d.Wq, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Y6, acc6, Aq6=A6, Wq6=W6)
+        B.basq_linear_fused(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, d.Wq, d.w_scale,
+                            d.w_zero, d.w_sum, d.out_bias, Y6f, ws, Wq6=W6)
+        torch.cuda.synchronize()
+        assert torch.equal(Aq2, Aq) and torch.equal(meta2, meta), "rotate_quant with and without the fp6 output"
+        res.a6, res.w6 = A6.cpu().numpy(), W6.cpu().numpy()
+        res.acc6, res.y6_bits, res.y6_fused_bits = acc6.cpu().numpy(), si.bf16_bits(Y6.cpu()), si.bf16_bits(Y6f.cpu())
+    return res
+
+
+def check_fp6_path(case: Case, g: GpuResult, *, row_blocks: Optional[np.ndarray] = None) -> None:
+    """The fp6 matrix-core path must give the bits of the int8 path (which check_parity ties to the
+    oracle), and both repacked operands must be the oracle's encoding of the same codes.
+    ``row_blocks``: compare only these 32-row blocks of the operands (full-size cases)."""
+    if g.a6 is None:
+        return
+    np.testing.assert_array_equal(g.acc6, g.acc, err_msg="INT32 accumulators, fp6 path vs int8 path")
+    np.testing.assert_array_equal(g.y6_bits, g.y_bits, err_msg="outputs, fp6 path vs int8 path")
+    np.testing.assert_array_equal(g.y6_fused_bits, g.y_bits, err_msg="basq_linear_fused on the fp6 path")
+    for name, buf, codes in (("activations", g.a6, g.codes), ("weights", g.w6, case.wq.codes)):
+        R, K = codes.shape
+        RB = (R + 31) // 32
+        if row_blocks is not None:
+            blocks = np.asarray([b for b in row_blocks if b < RB])
+        elif R * K <= (1 << 20):
+            blocks = np.arange(RB)
+        else:                                       # the encoder here is a Python loop: first, middle and last block
+            blocks = np.unique([0, RB // 2, RB - 1])
+        got = buf.reshape(K // 128, RB, 3072)
+        for rb in blocks:
+            rows = codes[32 * rb:32 * rb + 32]
+            ref = oracle.pack_fp6(np.ascontiguousarray(rows)).reshape(K // 128, 1, 3072)[:, 0]
+            n = rows.shape[0]
+            if n == 32:
+                np.testing.assert_array_equal(got[:, rb], ref, err_msg=f"fp6 form of the {name}, row block {rb}")
+            else:                                   # ragged last block: only the bytes of real rows are defined
+                mask = oracle.pack_fp6(np.full((n, K), 15, dtype=np.uint8)).reshape(K // 128, 3072) != 0
+                mask |= oracle.pack_fp6(np.full((n, K), 1, dtype=np.uint8)).reshape(K // 128, 3072) != 0
+                np.testing.assert_array_equal(got[:, rb][mask], ref[mask], err_msg=f"fp6 form of the {name}, last block")
 
 
 def check_parity(case: Case, g: GpuResult, *, rows: Optional[np.ndarray] = None, use_blas_gemm: bool = False,

@@ -76,6 +76,34 @@ def run_fullsize(name, n_rows, n_cols, M=None):
     torch.cuda.synchronize()
     assert torch.equal(Y, Yf), "fused call differs from the two-call path"
 
+    # ---- the fp6 matrix-core path (what bench.py times for prefill shapes): same bits everywhere
+    if M > 16:
+        Wq6 = B.alloc_fp6_buffer(N, K, dev)
+        B.basq_pack_fp6(Wq, Wq6)
+        Aq6 = B.alloc_fp6_buffer(M, K, dev)
+        Aq2, meta2 = B.alloc_activation_buffers(M, K, dev)
+        B.basq_rotate_quant(X, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq2, meta2, None, Aq6=Aq6)
+        acc6 = torch.empty((M, N), dtype=torch.int32, device=dev)
+        Y6 = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        B.basq_w4a4_gemm(Aq2, meta2, Wq, w_scale, w_zero, w_sum, out_bias, Y6, acc6, Aq6=Aq6, Wq6=Wq6)
+        Y6f = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        B.basq_linear_fused(X, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Wq, w_scale, w_zero, w_sum, out_bias, Y6f, wsf,
+                            Wq6=Wq6)
+        torch.cuda.synchronize()
+        assert torch.equal(Aq2, Aq) and torch.equal(meta2, meta)
+        assert torch.equal(acc6, acc), "INT32 accumulators of the fp6 path differ from the int8 path"
+        assert torch.equal(Y6, Y) and torch.equal(Y6f, Y), "outputs of the fp6 path differ from the int8 path"
+        # both repacked operands against the oracle's encoder, on three 32-row blocks each
+        for name6, buf, packed in (("activations", Aq6, Aq), ("weights", Wq6, Wq)):
+            R = packed.shape[0]
+            RB = (R + 31) // 32
+            got = buf.view(K // 128, RB, 3072)
+            for rb in sorted({0, RB // 2, R // 32 - 1}):
+                codes_rb = oracle.unpack_codes(packed[32 * rb:32 * rb + 32].cpu().numpy())
+                ref6 = oracle.pack_fp6(codes_rb).reshape(K // 128, 3072)
+                np.testing.assert_array_equal(got[:, rb].cpu().numpy(), ref6, err_msg=f"fp6 form of the {name6}, block {rb}")
+        del Wq6, Aq6, Aq2, meta2, acc6, Y6, Y6f
+
     t_rows = torch.from_numpy(rows).to(dev)
     t_cols = torch.from_numpy(cols).to(dev)
     # weights of the sampled channels: bit-exact

@@ -29,6 +29,7 @@ def run_case(lay, **kw):
     d = pu.to_device(case)
     g = pu.run_gpu(case, d)
     stats = pu.check_parity(case, g, rows=rows, use_blas_gemm=blas)
+    pu.check_fp6_path(case, g)
     announce(f"ok {stats}")
     return stats
 
