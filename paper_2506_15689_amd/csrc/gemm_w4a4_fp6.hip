@@ -54,14 +54,24 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
     static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32-row blocks");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     static_assert(STAGES == 2 || STAGES == 3, "the wait counts below assume at most one stage in flight beyond the next");
+    static_assert((BM + BN) * 16 <= STAGE_BYTES, "the epilogue constants live in the last stage");
 
     __shared__ __attribute__((aligned(1024))) uint8_t lds[STAGES * STAGE_BYTES];
 
-    // ---- tile assignment (XCD-aware: ids congruent mod 8 run on one XCD and walk a compact band)
-    int tile_m, tile_n;
-    {
-        const int total = tiles_m * tiles_n;
-        const int pid = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int swave = __builtin_amdgcn_readfirstlane(wave);
+    const int ksteps = a.K / 128;
+    const int rb_a = (int)((a.M + 31) >> 5), rb_w = (a.N + 31) >> 5;   // 32-row blocks per chunk of K
+    const unsigned a_step = (unsigned)rb_a * BLOCK, w_step = (unsigned)rb_w * BLOCK;   // bytes from one chunk of K to the next
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Aq6), 0, (int)(a_step * (unsigned)ksteps), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Wq6), 0, (int)(w_step * (unsigned)ksteps), 0x00020000);
+
+    // ---- tile order (XCD-aware: workgroups congruent mod 8 run on one XCD; the tiles a workgroup takes,
+    // blockIdx.x + i * gridDim.x, stay congruent when the grid is a multiple of 8 and walk a compact band)
+    const int total = tiles_m * tiles_n;
+    auto tile_of = [&](int pid, int& tile_m, int& tile_n) {
         int t = pid;
         const int per_xcd = total / NUM_XCD;
         if (pid < per_xcd * NUM_XCD) t = (pid % NUM_XCD) * per_xcd + pid / NUM_XCD;
@@ -72,47 +82,45 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         const int in_band = t - band * GROUP_M * tiles_n;
         tile_m = first_m + in_band % rows;
         tile_n = in_band / rows;
-    }
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int64_t m0 = (int64_t)tile_m * BM;
-    const int n0 = tile_n * BN;
-    const int ksteps = a.K / 128;
-    const int rb_a = (int)((a.M + 31) >> 5), rb_w = (a.N + 31) >> 5;   // 32-row blocks per chunk of K
-    const unsigned a_step = (unsigned)rb_a * BLOCK, w_step = (unsigned)rb_w * BLOCK;   // bytes from one chunk of K to the next
+    };
 
     // ---- direct loads: load i of wave w copies the 1 KB piece number i*WAVES + w of the stage; three
-    // pieces make one 32-row block.  Blocks past the matrix are clamped to its last block.
-    const int swave = __builtin_amdgcn_readfirstlane(wave);
-    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Aq6), 0, (int)(a_step * (unsigned)ksteps), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(a.Wq6), 0, (int)(w_step * (unsigned)ksteps), 0x00020000);
-    int voff[LOADS];
+    // pieces make one 32-row block.  Which block a piece comes from is uniform over the wave, so it goes
+    // into the scalar offset of the load; the only per-lane part is 16 * lane.  Blocks past the matrix
+    // are clamped to its last block.
+    const int lane_off = lane * 16;
+    int soff[LOADS];                                           // scalar: block and part of each of this wave's pieces
+    auto set_tile = [&](int tile_m, int tile_n) {
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int piece = i * WAVES + wave;
-        int blk = piece / 3;
-        const int part = piece % 3;
-        if (piece < A_PIECES) {
-            blk += (int)(m0 >> 5);
-            blk = blk < rb_a ? blk : rb_a - 1;
-        } else {
-            blk += (n0 >> 5) - BM / 32;
-            blk = blk < rb_w ? blk : rb_w - 1;
+        for (int i = 0; i < LOADS; ++i) {
+            const int piece = i * WAVES + swave;
+            int blk = piece / 3;
+            const int part = piece % 3;
+            if (piece < A_PIECES) {
+                blk += tile_m * (BM / 32);
+                blk = blk < rb_a ? blk : rb_a - 1;
+            } else {
+                blk += tile_n * (BN / 32) - BM / 32;
+                blk = blk < rb_w ? blk : rb_w - 1;
+            }
+            soff[i] = blk * BLOCK + part * 1024;
         }
-        voff[i] = blk * BLOCK + part * 1024 + lane * 16;
-    }
+    };
     auto issue_loads = [&](int ks) {
         uint8_t* stage = lds + (ks % STAGES) * STAGE_BYTES + swave * 1024;
-        const int koff_a = (int)((unsigned)ks * a_step), koff_w = (int)((unsigned)ks * w_step);   // unsigned 32-bit byte offsets
+        const unsigned koff_a = (unsigned)ks * a_step, koff_w = (unsigned)ks * w_step;   // unsigned 32-bit byte offsets
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             if (i * WAVES + swave < A_PIECES)                    // uniform over the wave
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, voff[i], koff_a, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_a + (unsigned)soff[i]), 0, 0);
             else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, voff[i], koff_w, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_w + (unsigned)soff[i]), 0, 0);
         }
+    };
+    auto issue_prologue = [&]() {
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < ksteps) issue_loads(s);
     };
 
     // ---- fragment addressing: lane (frow, fhalf) feeds k = 64*kb + 32*fhalf .. +31 of its row, i.e.
@@ -126,32 +134,6 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
     }
     const int a_row = (wm * WM / 32) * BLOCK;
     const int b_row = (BM / 32 + wn * WN / 32) * BLOCK;
-
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    // ---- prologue: fill STAGES-1 stages
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < ksteps) issue_loads(s);
-    // at most (STAGES-2) later stages may still be in flight when stage 0 is needed
-    if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
-
-    // Operand registers: six consecutive VGPRs per fragment (the builtin takes eight; the fp6 form of
-    // the instruction reads the first six).  The two LDS reads of a fragment land in them directly.
-    v8i pa[2][TM], pb[2][TN];
-#pragma unroll
-    for (int set = 0; set < 2; ++set) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) pa[set][i] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < TN; ++j) pb[set][j] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
-    }
     // Byte offsets of the 8-byte tail reads, one opaque register each: reads whose addresses share a
     // visible base get merged into paired reads, whose result could not land in two operand tuples
     // without register copies.
@@ -163,134 +145,201 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
 #pragma unroll
         for (int j = 0; j < TN; ++j) { tb[kb][j] = b_row + j * BLOCK + toff[kb]; asm volatile("" : "+v"(tb[kb][j])); }
     }
-    auto read_one = [&](v8i& dst, const uint8_t* main_ptr, const uint8_t* tail_ptr) {
-        const v4i m = *reinterpret_cast<const v4i*>(main_ptr);
-        const v2i t = *reinterpret_cast<const v2i*>(tail_ptr);
-        dst[0] = m[0]; dst[1] = m[1]; dst[2] = m[2]; dst[3] = m[3]; dst[4] = t[0]; dst[5] = t[1];
-    };
-    auto read_frags = [&](const uint8_t* st, int kb, int set) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) read_one(pa[set][i], st + a_row + i * BLOCK + moff[kb], st + ta[kb][i]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) read_one(pb[set][j], st + b_row + j * BLOCK + moff[kb], st + tb[kb][j]);
-    };
-    auto compute = [&](int set) {
+
+    // epilogue constants: in the last stage of the ring, which the next tile's first loads do not touch
+    float4* lrow_par = reinterpret_cast<float4*>(lds + (STAGES - 1) * STAGE_BYTES);
+    float4* lcol_par = lrow_par + BM;
+
+    // ---- persistent loop over this workgroup's tiles
+    int pid = blockIdx.x;
+    int tile_m, tile_n;
+    tile_of(pid, tile_m, tile_n);
+    set_tile(tile_m, tile_n);
+    issue_prologue();
+    bool first = true;
+    while (true) {
+        const int64_t m0 = (int64_t)tile_m * BM;
+        const int n0 = tile_n * BN;
+        v16f acc[TM][TN];
+        // Operand registers: six consecutive VGPRs per fragment (the builtin takes eight; the fp6 form of
+        // the instruction reads the first six).  The two LDS reads of a fragment land in them directly.
+        v8i pa[2][TM], pb[2][TN];
+    #pragma unroll
+        for (int set = 0; set < 2; ++set) {
+    #pragma unroll
+            for (int i = 0; i < TM; ++i) pa[set][i] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+    #pragma unroll
+            for (int j = 0; j < TN; ++j) pb[set][j] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+        auto read_one = [&](v8i& dst, const uint8_t* main_ptr, const uint8_t* tail_ptr) {
+            const v4i m = *reinterpret_cast<const v4i*>(main_ptr);
+            const v2i t = *reinterpret_cast<const v2i*>(tail_ptr);
+            dst[0] = m[0]; dst[1] = m[1]; dst[2] = m[2]; dst[3] = m[3]; dst[4] = t[0]; dst[5] = t[1];
+        };
+        auto read_frags = [&](const uint8_t* st, int kb, int set) {
+    #pragma unroll
+            for (int i = 0; i < TM; ++i) read_one(pa[set][i], st + a_row + i * BLOCK + moff[kb], st + ta[kb][i]);
+    #pragma unroll
+            for (int j = 0; j < TN; ++j) read_one(pb[set][j], st + b_row + j * BLOCK + moff[kb], st + tb[kb][j]);
+        };
+        auto compute = [&](int set) {
+    #pragma unroll
+            for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[set][i], pb[set][j], acc[i][j], 2, 2, 0, 0, 0, 0);
+        };
+
+
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[set][i], pb[set][j], acc[i][j], 2, 2, 0, 0, 0, 0);
-    };
-    read_frags(lds, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    for (int ks = 0; ks < ksteps; ++ks) {
-        const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
-        // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
-        if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
-        // kb = 0: read kb = 1 of this stage ahead
-        read_frags(st, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(0);
-        __builtin_amdgcn_sched_barrier(0);
-        // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
-        // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
-        if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
-        if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    __syncthreads();
+        // Stage 0 must have landed: on the first tile the loads of stage 1 may stay in flight; on later
+        // tiles both stages were waited for before the previous epilogue's stores went out.  The barrier
+        // also ends every wave's use of the epilogue constants before step 0 refills the last stage.
+        if (first) {
+            if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+        } else if (STAGES >= 3) {
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        } else {
+            wait_loads_and_barrier<0>();
+        }
+        first = false;
+        read_frags(lds, 0, 0);
 
-    // ---- epilogue: row and column constants through LDS (free now)
-    float4* lrow_par = reinterpret_cast<float4*>(lds);
-    float4* lcol_par = lrow_par + BM;
-    for (int i = tid; i < BM; i += THREADS) {
-        int64_t m = m0 + i;
-        m = m < a.M ? m : a.M - 1;
-        const basq_tokmeta mt = a.meta[m];
-        lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, 0.0f);
-    }
-    for (int i = tid; i < BN; i += THREADS) {
-        int n = n0 + i;
-        n = n < a.N ? n : a.N - 1;
-        lcol_par[i] = make_float4(bf16_to_f32(a.w_scale[n]), bf16_to_f32(a.w_zero[n]), a.w_sum[n],
-                                  a.out_bias ? a.out_bias[n] : 0.0f);
-    }
-    __syncthreads();
+        for (int ks = 0; ks < ksteps; ++ks) {
+            const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
+            // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
+            if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
+            // kb = 0: read kb = 1 of this stage ahead
+            read_frags(st, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(0);
+            __builtin_amdgcn_sched_barrier(0);
+            // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
+            // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
+            if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+            if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // every wave has passed the last step's barrier, after which nothing reads the ring: request the
+        // next tile's first stages now, so that their latency hides behind this tile's epilogue
+        const int next_pid = pid + gridDim.x;
+        const bool more = next_pid < total;
+        int next_m = 0, next_n = 0;
+        if (more) {
+            tile_of(next_pid, next_m, next_n);
+            set_tile(next_m, next_n);
+            if (STAGES >= 3) issue_prologue();            // with two stages the constants would be overwritten
+        }
 
-    const int col_in_tile = lane & 31, rgrp = lane >> 5;
-    float4 cp[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
+        // ---- epilogue: row and column constants through LDS
+        for (int i = tid; i < BM; i += THREADS) {
+            int64_t m = m0 + i;
+            m = m < a.M ? m : a.M - 1;
+            const basq_tokmeta mt = a.meta[m];
+            lrow_par[i] = make_float4(mt.scale, mt.lo, (float)mt.rowsum, 0.0f);
+        }
+        for (int i = tid; i < BN; i += THREADS) {
+            int n = n0 + i;
+            n = n < a.N ? n : a.N - 1;
+            lcol_par[i] = make_float4(bf16_to_f32(a.w_scale[n]), bf16_to_f32(a.w_zero[n]), a.w_sum[n],
+                                      a.out_bias ? a.out_bias[n] : 0.0f);
+        }
+        __syncthreads();
 
-    const bool vec_ok = a.acc_out == nullptr && (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
-    if (vec_ok) {
-        constexpr int PITCH = WN * 2 + 16;                      // bytes
-        constexpr int CH_PER_ROW = WN / 8;                      // 16-byte pieces per row
-        constexpr int PIECES = 32 * CH_PER_ROW / 64;            // per lane per 32-row block
-        constexpr int PARAM_BYTES = (BM + BN) * 16;
-        uint8_t* patch = lds + PARAM_BYTES + wave * (32 * PITCH);
-        static_assert(PARAM_BYTES % 16 == 0 && PARAM_BYTES + WAVES * 32 * PITCH <= STAGES * STAGE_BYTES, "epilogue staging does not fit");
+        // (re)derived per tile from an opaque copy of the lane index: everything computed from it below
+        // would otherwise be hoisted out of the tile loop and held in registers across the main loop
+        int elane = lane;
+        asm volatile("" : "+v"(elane));
+        const int col_in_tile = elane & 31, rgrp = elane >> 5;
+        float4 cp[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+        for (int j = 0; j < TN; ++j) cp[j] = lcol_par[wn * WN + j * 32 + col_in_tile];
+
+        // Pair path: two adjacent rows per step.  A lane turns its two values (same column, rows A and A+1)
+        // into one packed bf16 pair, trades it with the neighbouring column's lane (DPP), and a byte permute
+        // leaves even lanes with (row A; columns c, c+1) and odd lanes with (row A+1; columns c-1, c): every
+        // lane stores one dword, every half-wave 64-byte runs of two rows.
+        const bool pair_ok = a.acc_out == nullptr && (a.ldy & 1) == 0 && (a.N & 1) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 3) == 0;
+        if (pair_ok) {
+            typedef float f2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+            const int odd = elane & 1;
+            const unsigned sel = odd ? 0x03020706u : 0x05040100u;
+            // first every output dword into registers (they take the accumulators' place) ...
+            unsigned outv[TM][8][TN];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
-                const float4 rp = lrow_par[wm * WM + i * 32 + rloc];
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const float t = 4.0f * acc[i][j][r] - cp[j].y * rp.z;      // 4*S is the integer accumulator, exactly
-                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
-                    *reinterpret_cast<uint16_t*>(patch + rloc * PITCH + (j * 32 + col_in_tile) * 2) = f32_to_bf16(y);
-                }
-            }
-            // one wave's LDS operations complete in order: the reads below see the writes above
-            __builtin_amdgcn_wave_barrier();
+                for (int q = 0; q < 8; ++q) {
+                    const int rowA = 8 * (q >> 1) + 4 * rgrp + 2 * (q & 1);        // register 2q; register 2q+1 is the next row
+                    const float4 rpA = lrow_par[wm * WM + i * 32 + rowA];
+                    const float4 rpB = lrow_par[wm * WM + i * 32 + rowA + 1];
 #pragma unroll
-            for (int q = 0; q < PIECES; ++q) {
-                const int id = q * 64 + lane;
-                const int rloc = id / CH_PER_ROW, ch = id % CH_PER_ROW;
-                const uint4 v = *reinterpret_cast<const uint4*>(patch + rloc * PITCH + ch * 16);
-                const int64_t m = m0 + wm * WM + i * 32 + rloc;
-                const int n = n0 + wn * WN + ch * 8;
-                if (m < a.M) {
-                    uint16_t* dst = a.Y + m * a.ldy + n;
-                    if (n + 8 <= a.N) {
-                        *reinterpret_cast<uint4*>(dst) = v;
-                    } else {
-                        const uint16_t e[8] = {(uint16_t)v.x, (uint16_t)(v.x >> 16), (uint16_t)v.y, (uint16_t)(v.y >> 16),
-                                               (uint16_t)v.z, (uint16_t)(v.z >> 16), (uint16_t)v.w, (uint16_t)(v.w >> 16)};
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) if (n + u < a.N) dst[u] = e[u];
+                    for (int j = 0; j < TN; ++j) {
+                        const float tA = fmaf(4.0f, acc[i][j][2 * q], -(cp[j].y * rpA.z));      // 4*S is the integer accumulator, exactly
+                        const float tB = fmaf(4.0f, acc[i][j][2 * q + 1], -(cp[j].y * rpB.z));
+                        const float yA = fmaf(rpA.x * cp[j].x, tA, fmaf(rpA.y, cp[j].z, cp[j].w));
+                        const float yB = fmaf(rpB.x * cp[j].x, tB, fmaf(rpB.y, cp[j].z, cp[j].w));
+                        const unsigned mine = __builtin_bit_cast(unsigned, __builtin_convertvector((f2){yA, yB}, b2));   // hardware round-to-nearest-even
+                        const unsigned other = (unsigned)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // lane ^ 1
+                        outv[i][q][j] = __builtin_amdgcn_perm(other, mine, sel);
                     }
                 }
             }
-            __builtin_amdgcn_wave_barrier();
-        }
-        return;
-    }
+            // ... then wait for the next tile's first stages (requested before this epilogue, so mostly
+            // landed), and only then send the stores: a wait placed after them would have to wait for
+            // the stores too, the counter being one and the same
+            if (more && STAGES >= 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = wm * WM + i * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
-            const int64_t m = m0 + row;
-            if (m >= a.M) continue;
-            const float4 rp = lrow_par[row];
-            uint16_t* yrow = a.Y + m * a.ldy;
+                for (int q = 0; q < 8; ++q) {
+                    const int rowA = 8 * (q >> 1) + 4 * rgrp + 2 * (q & 1);
+                    const int64_t m = m0 + wm * WM + i * 32 + rowA + odd;
+                    uint16_t* yrow = a.Y + m * a.ldy + n0 + wn * WN + (col_in_tile & ~1);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * WN + j * 32 + col_in_tile;
-                if (n < a.N) {
-                    const int av = __float2int_rn(4.0f * acc[i][j][r]);
-                    const float t = (float)av - cp[j].y * rp.z;
-                    const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
-                    yrow[n] = f32_to_bf16(y);
-                    if (a.acc_out) a.acc_out[m * (int64_t)a.N + n] = av;
+                    for (int j = 0; j < TN; ++j) {
+                        const int n = n0 + wn * WN + j * 32 + (col_in_tile & ~1);
+                        if (m < a.M && n < a.N) *reinterpret_cast<uint32_t*>(yrow + j * 32) = outv[i][q][j];
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wm * WM + i * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
+                    const int64_t m = m0 + row;
+                    if (m >= a.M) continue;
+                    const float4 rp = lrow_par[row];
+                    uint16_t* yrow = a.Y + m * a.ldy;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int n = n0 + wn * WN + j * 32 + col_in_tile;
+                        if (n < a.N) {
+                            const int av = __float2int_rn(4.0f * acc[i][j][r]);
+                            const float t = (float)av - cp[j].y * rp.z;
+                            const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
+                            yrow[n] = f32_to_bf16(y);
+                            if (a.acc_out) a.acc_out[m * (int64_t)a.N + n] = av;
+                        }
+                    }
                 }
             }
         }
+        if (!more) break;
+        if (!pair_ok && STAGES >= 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // slow path: loads and stores alike
+        pid = next_pid; tile_m = next_m; tile_n = next_n;
+        if (STAGES < 3) issue_prologue();                 // two stages: only now is the ring free of the constants
     }
 #endif  // __HIP_DEVICE_COMPILE__
 }
@@ -300,7 +349,12 @@ int launch_fp6(const GemmArgs& a, hipStream_t s) {
     const int64_t tm = (a.M + BM - 1) / BM;
     const int64_t tn = ((int64_t)a.N + BN - 1) / BN;
     if (tm * tn > 0x7FFFFFFFll) return fail(BASQ_EINVAL, "w4a4_gemm: problem too large for one launch");
-    hipLaunchKernelGGL((gemm_w4a4_fp6_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, MINOCC>), dim3((unsigned)(tm * tn)),
+    // persistent workgroups: as many as the chip's 256 compute units hold at once (MINOCC waves per
+    // SIMD), each walking the tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+    const int64_t resident = 256 * (MINOCC * 4 / (WAVES_M * WAVES_N));
+    static_assert(MINOCC * 4 % (WAVES_M * WAVES_N) == 0 && MINOCC * 4 >= WAVES_M * WAVES_N, "whole workgroups per compute unit");
+    const int64_t grid = tm * tn < resident ? tm * tn : resident;
+    hipLaunchKernelGGL((gemm_w4a4_fp6_kernel<BM, BN, WAVES_M, WAVES_N, STAGES, MINOCC>), dim3((unsigned)grid),
                        dim3(WAVES_M * WAVES_N * 64), 0, s, a, (int)tm, (int)tn);
     return check_hip(hipGetLastError(), "w4a4_gemm (fp6) launch");
 }
