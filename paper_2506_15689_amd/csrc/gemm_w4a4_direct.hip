@@ -85,7 +85,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
     for (int i = 0; i < LOADS; ++i) {
         const int L = (i * WAVES + wave) * 64 + lane;
         const int row = L / NCH, cpos = L % NCH;
-        const int swz = (BKB == 128) ? (row & 7) : ((row >> 1) & 3);
+        const int swz = (BKB == 128) ? ((row >> 1) & 7) : ((row >> 2) & 3);   // 16 consecutive rows hit 16 distinct 16-byte bank groups
         const int c = cpos ^ swz;
         if (i < A_LOADS) {
             int64_t m = m0 + row;
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
 
     // ---- fragment addressing: lane (frow, fhalf) reads chunk fhalf + 2h of its row, swizzled
     const int frow = lane & 31, fhalf = lane >> 5;
-    const int fswz = (BKB == 128) ? (frow & 7) : ((frow >> 1) & 3);
+    const int fswz = (BKB == 128) ? ((frow >> 1) & 7) : ((frow >> 2) & 3);
     int foff[NCH / 2];
 #pragma unroll
     for (int h = 0; h < NCH / 2; ++h) foff[h] = (((fhalf + 2 * h) ^ fswz) << 4);
