@@ -33,8 +33,10 @@ FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
 # HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
 # under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
 MEASURED_TRAFFIC = {
-    ("C2", "rotate_quant"): 21264589, ("C2", "gemm"): 171217715,
-    ("C5", "rotate_quant"): 84447437, ("C5", "gemm"): 943563981,
+    ("C2", "rotate_quant"): 27570516, ("C2", "gemm"): 170408395, ("C2", "gemm_fp6"): 240840227,
+    ("C4", "rotate_quant"): 106123093, ("C4", "gemm"): 173675831, ("C4", "gemm_fp6"): 237421378,
+    ("C5", "rotate_quant"): 109653302, ("C5", "gemm"): 945002621, ("C5", "gemm_fp6"): 1294344815,
+    ("C3_M16", "rotate_quant"): 302253, ("C3_M16", "gemm"): 8981508,
 }
 
 
@@ -60,14 +62,17 @@ def parse_args():
     return p.parse_args()
 
 
-def algorithmic_bytes_rotate_quant(M, K):
-    # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes of token record out
-    return M * (2 * K + K // 2 + 16)
+def algorithmic_bytes_rotate_quant(M, K, fp6=False):
+    # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes of token record out, and 3K/4 bytes
+    # more when the codes are also written in the fp6 operand form
+    return M * (2 * K + K // 2 + 16 + (3 * K // 4 if fp6 else 0))
 
 
-def algorithmic_bytes_gemm(M, K, N):
-    # codes of both operands, token records, per-channel vectors, bf16 output
-    return M * (K // 2 + 16) + N * (K // 2) + N * (2 + 2 + 4 + 4) + 2 * M * N
+def algorithmic_bytes_gemm(M, K, N, fp6=False):
+    # codes of both operands (4 bits each, or 6 in the fp6 operand form), token records, per-channel
+    # vectors, bf16 output
+    per_code = 3 * K // 4 if fp6 else K // 2
+    return M * (per_code + 16) + N * per_code + N * (2 + 2 + 4 + 4) + 2 * M * N
 
 
 def cpu_baseline(cfg, lay, sample_tokens):
@@ -204,7 +209,7 @@ def main():
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
-    if args.M > 0 or args.no_bias:
+    if args.M > 0 or args.no_bias or (args.matrix_path == "int8" and M > 16):
         MEASURED_TRAFFIC.clear()                  # the stored counters belong to the unmodified configurations
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -247,8 +252,8 @@ def main():
         ceilings["fp6_mfma_TOPS"] = 512 * 4 * 8 * iters * 131072.0 / (ms * 1e-3) / 1e12
         del fout
 
-    rq_bytes = algorithmic_bytes_rotate_quant(M, K)
-    gemm_bytes = algorithmic_bytes_gemm(M, K, N)
+    rq_bytes = algorithmic_bytes_rotate_quant(M, K, use_fp6)
+    gemm_bytes = algorithmic_bytes_gemm(M, K, N, use_fp6)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     decode = M <= 16
     if rq_only:
