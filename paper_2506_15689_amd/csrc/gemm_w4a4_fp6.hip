@@ -48,9 +48,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int ROWS = BM + BN;
     constexpr int STAGE_BYTES = ROWS * CHUNK;
-    constexpr int LOADS = STAGE_BYTES / (WAVES * 1024);       // direct loads (1 KB per wave) per thread per stage
-    constexpr int A_PIECES = BM * CHUNK / 1024;               // 1 KB pieces 0 .. A_PIECES-1 of a stage are activations
-    static_assert(STAGE_BYTES % (WAVES * 1024) == 0, "stage does not divide over the waves");
+    constexpr int PIECES = STAGE_BYTES / 1024;                // 1 KB pieces of a stage, one wave-load each
+    constexpr int LOADS = (PIECES + WAVES - 1) / WAVES;       // direct loads per thread per stage (the last one may be idle)
+    constexpr int MIN_LOADS = PIECES / WAVES;                 // ... that every wave really issues: what the partial waits count
+    constexpr int A_PIECES = BM * CHUNK / 1024;               // pieces 0 .. A_PIECES-1 of a stage are activations
+    static_assert(STAGE_BYTES % 1024 == 0, "a stage is a whole number of 1 KB pieces");
     static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32-row blocks");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     static_assert(STAGES == 2 || STAGES == 3, "the wait counts below assume at most one stage in flight beyond the next");
@@ -111,7 +113,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         const unsigned koff_a = (unsigned)ks * a_step, koff_w = (unsigned)ks * w_step;   // unsigned 32-bit byte offsets
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            if (i * WAVES + swave < A_PIECES)                    // uniform over the wave
+            if (i * WAVES + swave >= PIECES) continue;           // (uniform over the wave, like the next test)
+            if (i * WAVES + swave < A_PIECES)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_a + (unsigned)soff[i]), 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_w + (unsigned)soff[i]), 0, 0);
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         // tiles both stages were waited for before the previous epilogue's stores went out.  The barrier
         // also ends every wave's use of the epilogue constants before step 0 refills the last stage.
         if (first) {
-            if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+            if (STAGES >= 3 && ksteps > 1) wait_loads_and_barrier<MIN_LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
         } else if (STAGES >= 3) {
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         } else {
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
             __builtin_amdgcn_sched_barrier(0);
             // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
             // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
-            if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
+            if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<MIN_LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
             if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             compute(1);

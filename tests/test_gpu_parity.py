@@ -45,6 +45,13 @@ def test_ragged_multi_tile(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=M))
 
 
+@pytest.mark.parametrize("M,K,N", [(17, 128, 8), (40, 384, 264), (290, 640, 130)])
+def test_short_k_on_the_fp6_path(M, K, N):
+    """One, three and five K-steps of the fp6 GEMM's stage ring (its prologue fills two stages), M just above
+    the decode threshold, N below one MFMA tile."""
+    run_case(si.make_tiny(M, K, N, seed=K + M), rot_size=128)
+
+
 @pytest.mark.parametrize("K,rot", [(1024, 128), (512, 64), (256, 32), (64, 2)])
 def test_blockwise_rotation(K, rot):
     run_case(si.make_tiny(48, K, 64, seed=K + rot), rot_size=rot)
