@@ -119,9 +119,9 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
 /*
  * The fp6 operand form of an INT4 code matrix (device-side repacking; offline for weights).
  * The matrix cores of this GPU multiply 6-bit floating-point operands (e2m3: sign, 2 exponent bits,
- * 3 mantissa bits) at twice their int8 rate.  Code q in 0..15 is stored as the e2m3 number q/2, which
- * is exact; S = sum_k (qa/2)(qb/2) is exact in the fp32 accumulator for K <= 32768, and the INT32
- * accumulator of the INT4 GEMM (Sec. 5.2) is 4*S.
+ * 3 mantissa bits) at twice their int8 rate.  Code q in 0..15 is stored as the e2m3 number q/8, which
+ * is exact; S = sum_k (qa/8)(qb/8) is exact in the fp32 accumulator for K <= 32768, and the INT32
+ * accumulator of the INT4 GEMM (Sec. 5.2) is 64*S.  (The e2m3 bit pattern of q/8 is q itself.)
  *
  *   codes      device uint8 [rows, K/2], two codes per byte, low nibble first (as Aq and Wq)
  *   out6       out, device uint8, basq_fp6_bytes(rows, K) bytes, 16-byte aligned.  Blocks of 3072

@@ -132,7 +132,7 @@ def unpack_codes(p: np.ndarray) -> np.ndarray:
 # here from the format's definition so that the repacking kernels can be checked bit by bit.
 #   e2m3 (OCP Microscaling FP6): 1 sign bit, 2 exponent bits (bias 1), 3 mantissa bits, no Inf/NaN;
 #   value = (-1)^s * 2^(e-1) * (1 + m/8) for e > 0, (-1)^s * (m/8) for e = 0.
-#   Code q is stored as the number q/2.
+#   Code q is stored as the number q/8.
 # ------------------------------------------------------------------------------------------------
 def e2m3_value(code: int) -> float:
     """Value of a 6-bit e2m3 pattern, from the format definition."""
@@ -143,10 +143,10 @@ def e2m3_value(code: int) -> float:
 
 @functools.lru_cache(maxsize=None)
 def e2m3_code_table() -> tuple:
-    """The e2m3 pattern whose value is q/2, for q = 0..15 (found by searching the 64 patterns; +0 for 0)."""
+    """The e2m3 pattern whose value is q/8, for q = 0..15 (found by searching the 64 patterns; +0 for 0)."""
     table = []
     for q in range(16):
-        hits = [c for c in range(64) if e2m3_value(c) == q / 2.0 and not (c >> 5)]
+        hits = [c for c in range(64) if e2m3_value(c) == q / 8.0 and not (c >> 5)]
         assert len(hits) == 1, (q, hits)
         table.append(hits[0])
     return tuple(table)

@@ -62,9 +62,9 @@ __global__ __launch_bounds__(256) void diag_mfma_kernel(int* out, int iters) {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// six-bit fields of a dword pattern forced into the range of the codes' encodings (0..31: the e2m3 values
-// 0 .. 7.5 that stand for q/2); field boundaries do not matter for a throughput loop, only realistic bits
-__device__ __forceinline__ int fp6_bits(int x) { return x & 0x7DF7DF7D; }
+// six-bit fields of a dword pattern forced into the range of the codes' encodings (0..15: the e2m3 values
+// q/8); field boundaries do not matter for a throughput loop, only realistic bits
+__device__ __forceinline__ int fp6_bits(int x) { return x & 0x3CF3CF3C; }
 
 __global__ __launch_bounds__(256) void diag_mfma_f6_kernel(float* out, int iters) {
     v16f acc[4];

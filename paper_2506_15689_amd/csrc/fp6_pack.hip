@@ -1,9 +1,11 @@
 // INT4 codes -> the 6-bit floating-point operand form of the matrix core.
 //
-// A code q in 0..15 is stored as the e2m3 number q/2 (sign, 2 exponent bits, 3 mantissa bits; every
-// multiple of 1/2 up to 7.5 is exact), so that the f8f6f4 MFMA, twice as fast as the int8 one, accumulates
-// S = sum_k (qa/2)(qb/2) exactly in fp32 (multiples of 1/4 below 2^21 for K <= 32768).  The INT32
-// accumulator of the paper's INT4 GEMM (Sec. 5.2) is 4*S.
+// A code q in 0..15 is stored as the e2m3 number q/8 (sign, 2 exponent bits, 3 mantissa bits).  Its bit
+// pattern is q itself: below 8 the number is subnormal with mantissa q, from 8 on the exponent field is 1
+// and the mantissa q - 8.  The f8f6f4 MFMA, twice as fast as the int8 one, then accumulates
+// S = sum_k (qa/8)(qb/8) exactly in fp32 (multiples of 1/64 below 2^17 for K <= 32768), and the INT32
+// accumulator of the paper's INT4 GEMM (Sec. 5.2) is 64*S.  (q/2 and q/4 are exact as well; q/8 keeps the
+// two upper bits of every field zero, which the matrix cores reward with a few percent more throughput.)
 //
 // Layout: blocks of 3072 bytes, one per (chunk of 128 codes along K, block of 32 rows), chunk-major:
 // block (c, rb) sits at ((c * ceil(rows/32)) + rb) * 3072.  It is the image the GEMM wants in LDS, so a
@@ -17,16 +19,6 @@
 namespace basq {
 
 namespace {
-
-// e2m3 encoding of q/2: 0 -> 0; 1/2 is the subnormal 0.100b; from 1 on, exponent field 1 + floor(log2(q/2))
-// and the three bits below the leading one.  q >= 8 (values 4 .. 7.5, step 1/2) is 24 + (q - 8).
-__device__ __forceinline__ uint32_t fp6_of_code(uint32_t q) {
-    // one byte per code, 16 codes in two 64-bit words
-    constexpr uint64_t T0 = 0x161412100C080400ull;            // q = 0..7 : 0, 4, 8, 12, 16, 18, 20, 22
-    constexpr uint64_t T1 = 0x1F1E1D1C1B1A1918ull;            // q = 8..15: 24 .. 31
-    const uint64_t t = q < 8u ? T0 : T1;
-    return (uint32_t)(t >> (8u * (q & 7u))) & 0x3Fu;
-}
 
 __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict__ codes, int64_t rows, int32_t K,
                                                         uint8_t* __restrict__ out6) {
@@ -46,7 +38,7 @@ __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
             const uint32_t q = (w[e >> 3] >> (4 * (e & 7))) & 0xFu;
-            const uint32_t c = fp6_of_code(q);
+            const uint32_t c = q;                                 // the e2m3 pattern of q/8
             const int bit = 6 * e;
             o[bit >> 5] |= c << (bit & 31);
             if ((bit & 31) > 26) o[(bit >> 5) + 1] |= c >> (32 - (bit & 31));

@@ -1,9 +1,9 @@
 // Prefill INT4 x INT4 -> INT32 GEMM on the f8f6f4 matrix-core path (paper Sec. 5.2; Fig. 6; Eq. 14).
 //
-// Both operands arrive in the fp6 operand form of fp6_pack.hip: code q stored as the e2m3 number q/2.
+// Both operands arrive in the fp6 operand form of fp6_pack.hip: code q stored as the e2m3 number q/8.
 // v_mfma_f32_32x32x64_f8f6f4 with two fp6 operands runs at twice the int8 rate and its fp32 accumulator
-// holds S = sum_k (qa/2)(qb/2) exactly (multiples of 1/4, S < 2^21 for K <= 32768).  The integer
-// accumulator of the INT4 product is ACC = 4*S; the epilogue de-quantises exactly as the int8 kernels do.
+// holds S = sum_k (qa/8)(qb/8) exactly (multiples of 1/64, S < 2^17 for K <= 32768).  The integer
+// accumulator of the INT4 product is ACC = 64*S; the epilogue de-quantises exactly as the int8 kernels do.
 //
 // Structure as in gemm_w4a4_direct.hip: direct-to-LDS buffer loads into a ring of stages, fragments
 // read one step ahead into two register sets, XCD-aware tile order.  A stage holds 128 codes per row.
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
                     const float4 rpB = lrow_par[wm * WM + i * 32 + rowA + 1];
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
-                        const float tA = fmaf(4.0f, acc[i][j][2 * q], -(cp[j].y * rpA.z));      // 4*S is the integer accumulator, exactly
-                        const float tB = fmaf(4.0f, acc[i][j][2 * q + 1], -(cp[j].y * rpB.z));
+                        const float tA = fmaf(64.0f, acc[i][j][2 * q], -(cp[j].y * rpA.z));      // 64*S is the integer accumulator, exactly
+                        const float tB = fmaf(64.0f, acc[i][j][2 * q + 1], -(cp[j].y * rpB.z));
                         const float yA = fmaf(rpA.x * cp[j].x, tA, fmaf(rpA.y, cp[j].z, cp[j].w));
                         const float yB = fmaf(rpB.x * cp[j].x, tB, fmaf(rpB.y, cp[j].z, cp[j].w));
                         const unsigned mine = __builtin_bit_cast(unsigned, __builtin_convertvector((f2){yA, yB}, b2));   // hardware round-to-nearest-even
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
                     for (int j = 0; j < TN; ++j) {
                         const int n = n0 + wn * WN + j * 32 + col_in_tile;
                         if (n < a.N) {
-                            const int av = __float2int_rn(4.0f * acc[i][j][r]);
+                            const int av = __float2int_rn(64.0f * acc[i][j][r]);
                             const float t = (float)av - cp[j].y * rp.z;
                             const float y = fmaf(rp.x * cp[j].x, t, fmaf(rp.y, cp[j].z, cp[j].w));
                             yrow[n] = f32_to_bf16(y);

@@ -303,7 +303,7 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                 words[jb][r] = ev | (od << 4);
             }
             if (a.Aq6 && row_valid && tok_valid) {
-                // The 32 codes of group jb once more, as e2m3 numbers q/2 (the packed conversion divides by
+                // The 32 codes of group jb once more, as e2m3 numbers q/8 (the packed conversion divides by
                 // its scale operand and interleaves even and odd codes).  A lane's 128 channels are one
                 // 128-code chunk of the fp6 layout: chunk 4*i' + g, group jb.
                 v16f qe, qo;
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                         qe[4 * r + p] = (float)((words[jb][r] >> (8 * p)) & 0xFu);
                         qo[4 * r + p] = (float)((words[jb][r] >> (8 * p + 4)) & 0xFu);
                     }
-                const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 2.0f);
+                const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 8.0f);
                 const int rr = (int)(m & 31);
                 uint8_t* blk = a.Aq6 + ((int64_t)(4 * ip + g) * rb6 + (m >> 5)) * 3072;
                 *reinterpret_cast<uint4*>(blk + 64 * rr + 16 * (jb ^ ((rr >> 2) & 3))) =

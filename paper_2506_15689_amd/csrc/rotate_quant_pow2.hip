@@ -305,7 +305,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
                 if (a.Aq6) {
-                    // the same 32 codes as e2m3 numbers q/2: the packed conversion divides by its scale
+                    // the same 32 codes as e2m3 numbers q/8: the packed conversion divides by its scale
                     // operand and interleaves its two sources (even and odd codes)
                     v16f qe, qo;
 #pragma unroll
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                             qe[4 * w + j] = (float)((evs[w] >> (8 * j)) & 0xFFu);
                             qo[4 * w + j] = (float)((ods[w] >> (8 * j)) & 0xFFu);
                         }
-                    const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 2.0f);
+                    const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 8.0f);
                     // group 128*hf + 64*b + lane of the token: chunk (group / 4), position (group % 4)
                     const int g = 128 * hf + 64 * b + lane, f = g & 3, r = (int)(m & 31);
                     uint8_t* blk = a.Aq6 + ((int64_t)(g >> 2) * rb6 + (m >> 5)) * 3072;

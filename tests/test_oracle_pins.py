@@ -484,19 +484,20 @@ def test_e2m3_format_facts():
 
 def test_codes_are_exact_in_e2m3_and_products_sum_exactly_in_fp32():
     table = oracle.e2m3_code_table()
-    assert [oracle.e2m3_value(c) for c in table] == [q / 2.0 for q in range(16)]
-    assert len(set(table)) == 16 and all(c < 32 for c in table)            # distinct, sign bit clear
-    # worst case of the accumulator: K = 32768 products of 7.5 * 7.5, added one by one in fp32
-    acc = np.float32(0.0)
-    step = np.float32(7.5) * np.float32(7.5)
+    assert [oracle.e2m3_value(c) for c in table] == [q / 8.0 for q in range(16)]
+    assert table == tuple(range(16))                # the pattern of q/8 is q: subnormals below 8, exponent field 1 from 8 on
+    # q/2 and q/4 would be exact too (any of the three scalings fits the format)
+    vals = {oracle.e2m3_value(c) for c in range(32)}
+    assert all(q / 2.0 in vals and q / 4.0 in vals for q in range(16))
+    # worst case of the accumulator: K = 32768 products of (15/8)^2, added one by one in fp32
+    step = np.float32(1.875) * np.float32(1.875)
     run = np.cumsum(np.full(32768, step, dtype=np.float32), dtype=np.float32)
-    assert run[-1] == np.float32(56.25 * 32768) and (np.diff(run.astype(np.float64)) == 56.25).all()
-    # and a random row pair: 4 * (fp32 running sum of (qa/2)(qb/2)) is the integer dot product at every step
+    assert run[-1] == np.float32(3.515625 * 32768) and (np.diff(run.astype(np.float64)) == 3.515625).all()
+    # and a random row pair: 64 * (fp32 running sum of (qa/8)(qb/8)) is the integer dot product at every step
     rng = np.random.default_rng(11)
     qa, qb = rng.integers(0, 16, 32768), rng.integers(0, 16, 32768)
-    run = np.cumsum((qa / 2.0).astype(np.float32) * (qb / 2.0).astype(np.float32), dtype=np.float32)
-    np.testing.assert_array_equal(4.0 * run.astype(np.float64), np.cumsum(qa * qb))
-    del acc
+    run = np.cumsum((qa / 8.0).astype(np.float32) * (qb / 8.0).astype(np.float32), dtype=np.float32)
+    np.testing.assert_array_equal(64.0 * run.astype(np.float64), np.cumsum(qa * qb))
 
 
 def test_fp6_layout_round_trip_and_placement():
@@ -504,17 +505,17 @@ def test_fp6_layout_round_trip_and_placement():
     q = rng.integers(0, 16, (45, 384), dtype=np.uint8)                     # a ragged second row block
     buf = oracle.pack_fp6(q)
     assert buf.shape == (64 * 384 * 3 // 4,)
-    np.testing.assert_array_equal(oracle.unpack_fp6(buf, 45, 384) * 2.0, q)
+    np.testing.assert_array_equal(oracle.unpack_fp6(buf, 45, 384) * 8.0, q)
     # one code alone: row 37 (block 1, r = 5), k = 128 + 64 + 3 (chunk 1, group 2, field 3)
     one = np.zeros((45, 384), dtype=np.uint8)
-    one[37, 195] = 9                                                        # 4.5 -> pattern 0b011001
+    one[37, 195] = 9                                                        # 9/8 -> pattern 0b001001
     b1 = oracle.pack_fp6(one)
     base = (1 * 2 + 1) * 3072
     where = base + 64 * 5 + 16 * (2 ^ 1) + (6 * 3) // 8                     # bits 18..23 of the string: byte 2, bit 2
-    assert np.flatnonzero(b1).tolist() == [where] and b1[where] == 0b011001 << 2
+    assert np.flatnonzero(b1).tolist() == [where] and b1[where] == 0b001001 << 2
     # a field in the last 8 bytes: field 30 starts at bit 180 = byte 22, bit 4 -> tail byte 6
     one[:] = 0
-    one[2, 30] = 15                                                         # 7.5 -> 0b011111
+    one[2, 30] = 15                                                         # 15/8 -> 0b001111
     b2 = oracle.pack_fp6(one)
     t = 2048 + 256 * 0 + 8 * 2 + 6
-    assert np.flatnonzero(b2).tolist() == [t, t + 1] and b2[t] == (0b011111 << 4) & 0xFF and b2[t + 1] == 0b011111 >> 4
+    assert np.flatnonzero(b2).tolist() == [t] and b2[t] == (0b001111 << 4) & 0xFF
