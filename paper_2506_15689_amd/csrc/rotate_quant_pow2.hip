@@ -143,7 +143,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     // range makes 32 consecutive tokens (one block of the fp6 output) meet in one L2, where their 8- and
     // 16-byte pieces merge into whole lines before they are written back.
     int vblock = blockIdx.x;
-    if ((gridDim.x & 63) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (a.Aq6 && (gridDim.x & 63) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
     const int wave_id = vblock * P2_WAVES + wave;
     const int wave_stride = gridDim.x * P2_WAVES;
     const int64_t rb6 = (a.M + 31) >> 5;                       // 32-row blocks per chunk of the fp6 output
