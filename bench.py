@@ -57,15 +57,20 @@ def parse_args():
     p.add_argument("--matrix-path", default="fp6", choices=["fp6", "int8"],
                    help="prefill GEMM on the f8f6f4 matrix-core path (codes repacked as exact fp6 values; default) "
                         "or on the int8 path; decode-sized M always streams the INT4 weights")
+    p.add_argument("--rot-size", type=int, default=0, help="with --only rotate_quant: rotation block instead of the workload's")
+    p.add_argument("--group-size", type=int, default=0,
+                   help="with --only rotate_quant: channels per range (0 = per token); 128 with --rot-size 128 is the "
+                        "per-head quantiser of q, k and the KV cache")
     p.add_argument("--only", default="", choices=["", "rotate_quant"],
                    help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
     return p.parse_args()
 
 
-def algorithmic_bytes_rotate_quant(M, K, fp6=False):
-    # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes of token record out, and 3K/4 bytes
-    # more when the codes are also written in the fp6 operand form
-    return M * (2 * K + K // 2 + 16 + (3 * K // 4 if fp6 else 0))
+def algorithmic_bytes_rotate_quant(M, K, fp6=False, group=0):
+    # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes per record out (one per token, or one per
+    # group), and 3K/4 bytes more when the codes are also written in the fp6 operand form
+    records = 1 if group in (0, K) else K // group
+    return M * (2 * K + K // 2 + 16 * records + (3 * K // 4 if fp6 else 0))
 
 
 def algorithmic_bytes_gemm(M, K, N, fp6=False):
@@ -117,6 +122,11 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = si.CONFIGS[args.config]
+    if (args.rot_size or args.group_size) and args.only != "rotate_quant":
+        print("bench.py: --rot-size and --group-size go with --only rotate_quant (the GEMM takes per-token ranges)", file=sys.stderr)
+        sys.exit(2)
+    rot_size = args.rot_size if args.rot_size > 0 else cfg.rot_size
+    group = args.group_size
     M = args.M if args.M > 0 else cfg.M
     K, N = cfg.K, cfg.N
     lay = si.make_layer(cfg, M=M)
@@ -128,10 +138,10 @@ def main():
     Xc = lay.X_calib[:4096].to(dev)           # the bias is calibrated on at most 4096 tokens
     bias = torch.empty(K, dtype=torch.float32, device=dev)
     cal_ws = torch.empty(Xc.shape[0] * K, dtype=torch.float32, device=dev)
-    B.basq_calibrate_bias(Xc, cfg.rot_size, None, bias, cal_ws)
+    B.basq_calibrate_bias(Xc, rot_size, None, bias, cal_ws)
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
-    use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > 16
+    use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > 16 and group in (0, K)
     Wq6 = None
     if use_fp6:                                # offline: the weights once more in the fp6 operand form
         Wq6 = B.alloc_fp6_buffer(N, K, dev)
@@ -150,6 +160,8 @@ def main():
     for i in range(nsets):
         Xi = X0 if i == 0 else torch.roll(X0, shifts=i, dims=0).contiguous()
         Aq, meta = B.alloc_activation_buffers(M, K, dev)
+        if group not in (0, K):
+            meta = torch.empty((M * (K // group), 4), dtype=torch.int32, device=dev)
         Y = None if rq_only else torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         Aq6 = B.alloc_fp6_buffer(M, K, dev) if use_fp6 else None
         sets.append((Xi, Aq, meta, Y, Aq6))
@@ -160,7 +172,7 @@ def main():
 
     def rotate_quant(i):
         Xi, Aq, meta, _, Aq6 = sets[i % nsets]
-        B.basq_rotate_quant(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, Aq6=Aq6, stream=stream)
+        B.basq_rotate_quant(Xi, rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, Aq6=Aq6, group_size=group, stream=stream)
 
     def gemm(i):
         _, Aq, meta, Y, Aq6 = sets[i % nsets]
@@ -209,7 +221,7 @@ def main():
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
-    if args.M > 0 or args.no_bias or (args.matrix_path == "int8" and M > 16):
+    if args.M > 0 or args.no_bias or args.rot_size or args.group_size or (args.matrix_path == "int8" and M > 16):
         MEASURED_TRAFFIC.clear()                  # the stored counters belong to the unmodified configurations
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -252,7 +264,7 @@ def main():
         ceilings["fp6_mfma_TOPS"] = 512 * 4 * 8 * iters * 131072.0 / (ms * 1e-3) / 1e12
         del fout
 
-    rq_bytes = algorithmic_bytes_rotate_quant(M, K, use_fp6)
+    rq_bytes = algorithmic_bytes_rotate_quant(M, K, use_fp6, group)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N, use_fp6)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     decode = M <= 16
@@ -301,7 +313,7 @@ def main():
         "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if use_fp6 and not rq_only
                   else "int4 x int4 -> int32 (int8 MFMA)") + "; rotation and quantiser in f32; bf16 in/out",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": cfg.rot_size,
+        "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": rot_size, "group_size": group if group else K,
                    "clip": cfg.clip, "buffer_sets": nsets,
                    "matrix_path": "fp6" if use_fp6 else ("int8" if M > 16 else "int4 weight streaming")},
         "rotate_quant_GBps": rq_gbs,

@@ -77,9 +77,13 @@ const char* basq_last_error(void);
  *   bias       fp32 [K] b^c in the rotated basis, or NULL (= 0)
  *   act_scale  fp32 [K] s^a, or NULL (= 1)
  *   bits       must be 4 (else BASQ_EUNSUPPORTED)
- *   group_size 0 or K: one range per token.  Other values: BASQ_EUNSUPPORTED.
+ *   group_size 0 or K: one range and one record per token (what basq_w4a4_gemm consumes).  Otherwise a
+ *              multiple of 32 that divides K: every run of group_size consecutive channels gets its own
+ *              range, steps 4-6 above and the record apply per group (per-head quantisation of q, k and
+ *              the KV cache with rot_size = group_size = head_dim; Sec. 5 "Deployment Details").  Such
+ *              codes are not an input of basq_w4a4_gemm.
  *   Aq         out, uint8 [M, K/2] canonical packed codes
- *   meta       out, [M]
+ *   meta       out, [M, K/group_size] records, token-major (group_size 0 counts as K)
  *   rot_out    out, optional debug dump of r, fp32 [M, K]; NULL to skip
  *   Aq6        out, optional (NULL to skip): the same codes in the fp6 operand form described at
  *              basq_pack_fp6 (basq_fp6_bytes(M, K) bytes), 16-byte aligned; needs K % 128 == 0

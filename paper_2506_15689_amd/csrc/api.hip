@@ -46,8 +46,8 @@ int validate_rotate(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t ro
         return fail(BASQ_EUNSUPPORTED, "rot_size must be 2^t or 28*2^t with t >= 1 (got %d)", rot_size);
     if (K % rot_size != 0) return fail(BASQ_EINVAL, "K (%d) must be a multiple of rot_size (%d)", K, rot_size);
     if (bits != 4) return fail(BASQ_EUNSUPPORTED, "only bits == 4 is implemented (got %d)", bits);
-    if (group_size != 0 && group_size != K)
-        return fail(BASQ_EUNSUPPORTED, "only per-token ranges are implemented: group_size must be 0 or K (got %d)", group_size);
+    if (group_size != 0 && (group_size < 32 || group_size % 32 != 0 || K % group_size != 0))
+        return fail(BASQ_EINVAL, "group_size must be 0 or a multiple of 32 that divides K (got %d)", group_size);
     if (!(clip_lo > 0.0f) || !(clip_hi > 0.0f) || !(clip_lo <= 1.0f) || !(clip_hi <= 1.0f))
         return fail(BASQ_EINVAL, "clip ratios must be in (0, 1] (got %g, %g)", (double)clip_lo, (double)clip_hi);
     if (M > 0 && X == nullptr) return fail(BASQ_EINVAL, "X is null");
@@ -112,9 +112,12 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     if (!aligned16(Aq) || !aligned16(meta) || !aligned16(rot_out) || !aligned16(Aq6))
         return fail(BASQ_EINVAL, "Aq, meta, rot_out and Aq6 must be 16-byte aligned");
     if (Aq6 && K % 128 != 0) return fail(BASQ_EINVAL, "the fp6 operand form needs K %% 128 == 0 (got %d)", K);
+    if (Aq6 && group_size != 0 && group_size != K)
+        return fail(BASQ_EINVAL, "the fp6 operand form is the GEMM's, which takes per-token ranges only");
     a.X = static_cast<const uint16_t*>(X);
     a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
     a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
+    a.group = group_size == 0 ? K : group_size;
     a.Aq = Aq; a.meta = meta; a.rot_out = rot_out; a.Aq6 = Aq6;
     return launch_rotate_quant(a, static_cast<hipStream_t>(stream));
 }
@@ -161,6 +164,8 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     RotateQuantArgs a{};
     int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
     if (rc != BASQ_OK) return rc;
+    if (group_size != 0 && group_size != K)
+        return fail(BASQ_EUNSUPPORTED, "the GEMM takes per-token ranges only: group_size must be 0 or K (got %d)", group_size);
     rc = validate_fp6(nullptr, Wq6, false, K);
     if (rc != BASQ_OK) return rc;
     if (M == 0) {
@@ -183,6 +188,7 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     uint8_t* Aq6 = nullptr;
     if (Wq6 && M > 16)
         Aq6 = reinterpret_cast<uint8_t*>(meta) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
+    a.group = K;
     a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
     hipStream_t s = static_cast<hipStream_t>(stream);
     rc = launch_rotate_quant(a, s);
@@ -225,6 +231,7 @@ int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_
     a.X = static_cast<const uint16_t*>(X);
     a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
     a.clip_lo = a.clip_hi = 1.0f;
+    a.group = K;
     a.rot_out = static_cast<float*>(workspace);      // rotation-only mode: Aq/meta stay null
     hipStream_t s = static_cast<hipStream_t>(stream);
     rc = launch_rotate_quant(a, s);

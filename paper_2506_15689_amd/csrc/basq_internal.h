@@ -25,8 +25,9 @@ struct RotateQuantArgs {
     const float* bias;
     const float* act_scale;
     float clip_lo, clip_hi;
+    int32_t group;            // channels that share one range and one token record (K: the whole token)
     uint8_t* Aq;              // may be null in rot-only mode
-    basq_tokmeta* meta;       // may be null in rot-only mode
+    basq_tokmeta* meta;       // [M, K/group]; may be null in rot-only mode
     float* rot_out;           // optional
     uint8_t* Aq6;             // optional: the codes once more in the fp6 operand form (fp6_pack.hip)
 };
@@ -34,6 +35,9 @@ int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s);
 // register-resident kernel for rot_size == K in {4096, 8192} (rotate_quant_pow2.hip)
 bool rotate_quant_pow2_applicable(const RotateQuantArgs& a);
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s);
+// wave-local kernel for per-head work: rot_size == group == 128, K % 512 == 0 (rotate_quant_head.hip)
+bool rotate_quant_head_applicable(const RotateQuantArgs& a);
+int launch_rotate_quant_head(const RotateQuantArgs& a, hipStream_t s);
 // kernel for rot_size == K == 14336 = 28 * 512 (rotate_quant_k28.hip)
 bool rotate_quant_k28_applicable(const RotateQuantArgs& a);
 int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s);

@@ -138,6 +138,43 @@ __global__ __launch_bounds__(RQ_THREADS) void rotate_quant_generic_kernel(Rotate
     }
     if (a.Aq == nullptr) return;             // rotation-only mode (bias calibration)
 
+    if (a.group < K) {
+        // Group-wise ranges (per-head quantisation of q/k and of the KV cache, paper Sec. 5 "Deployment
+        // Details"): one thread per group walks its channels in LDS.  Plain fallback; the per-head shape
+        // rot_size = group = 128 has its own kernel.
+        __syncthreads();
+        const int G = a.group, ngroups = K / G;
+        for (int g = tid; g < ngroups; g += RQ_THREADS) {
+            const float* v = sm + g * G;
+            float gmn = INFINITY, gmx = -INFINITY;
+            for (int k = 0; k < G; ++k) { gmn = fminf(gmn, v[k]); gmx = fmaxf(gmx, v[k]); }
+            const float lo = a.clip_lo * gmn;
+            const float hi = a.clip_hi * gmx;
+            float s = __fdiv_rn(hi - lo, 15.0f);
+            if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
+            const float inv = __fdiv_rn(1.0f, s);
+            const float nlo = -(lo * inv);
+            int sum = 0;
+            uint32_t* arow = reinterpret_cast<uint32_t*>(a.Aq + m * (int64_t)(K / 2) + g * (G / 2));
+            for (int c = 0; c < G / 8; ++c) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    float t = fmaf(v[8 * c + j], inv, nlo);
+                    t = fminf(fmaxf(t, 0.0f), 15.0f);
+                    const int q = (int)rintf(t);
+                    sum += q;
+                    packed |= (uint32_t)q << (4 * j);
+                }
+                arow[c] = packed;
+            }
+            basq_tokmeta mt;
+            mt.scale = s; mt.lo = lo; mt.rowsum = sum; mt.reserved = 0;
+            a.meta[m * ngroups + g] = mt;
+        }
+        return;
+    }
+
     mn = wave_min(mn);
     mx = wave_max(mx);
     const int wave = tid >> 6, lane = tid & 63;
@@ -196,6 +233,7 @@ int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     // the two specialised kernels write the fp6 copy of the codes themselves
     if (rotate_quant_pow2_applicable(a)) return launch_rotate_quant_pow2(a, s);
     if (rotate_quant_k28_applicable(a)) return launch_rotate_quant_k28(a, s);
+    if (rotate_quant_head_applicable(a)) return launch_rotate_quant_head(a, s);
     const int rc = launch_rotate_quant_generic(a, s);
     if (rc != BASQ_OK || !a.Aq6 || !a.Aq) return rc;
     return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);

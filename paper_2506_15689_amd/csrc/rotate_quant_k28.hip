@@ -378,7 +378,7 @@ int launch_k28_flags(const RotateQuantArgs& a, hipStream_t s, float norm, const 
 }  // namespace
 
 bool rotate_quant_k28_applicable(const RotateQuantArgs& a) {
-    return a.has28 && a.rot_size == K28 && a.K == K28 && a.Aq != nullptr && a.meta != nullptr;
+    return a.group == a.K && a.has28 && a.rot_size == K28 && a.K == K28 && a.Aq != nullptr && a.meta != nullptr;
 }
 
 int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s) {

@@ -354,7 +354,7 @@ int launch_nc(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float no
 }  // namespace
 
 bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
-    return !a.has28 && a.rot_size == a.K && (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
+    return a.group == a.K && !a.has28 && a.rot_size == a.K && (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
 }
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {

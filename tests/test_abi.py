@@ -53,7 +53,9 @@ FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fa
     (dict(K=1024 + 512, ldx=2048, rot=1024), B.BASQ_EINVAL),
     (dict(bits=8), B.BASQ_EUNSUPPORTED),
     (dict(bits=3), B.BASQ_EUNSUPPORTED),
-    (dict(group=128), B.BASQ_EUNSUPPORTED),
+    (dict(group=100), B.BASQ_EINVAL),                                 # not a multiple of 32
+    (dict(group=96), B.BASQ_EINVAL),                                  # does not divide K
+    (dict(group=128, Aq6=FAKE), B.BASQ_EINVAL),                       # the fp6 form is per-token only
     (dict(clip_lo=0.0), B.BASQ_EINVAL),
     (dict(clip_hi=1.5), B.BASQ_EINVAL),
     (dict(clip_lo=float("nan")), B.BASQ_EINVAL),

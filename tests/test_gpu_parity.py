@@ -233,3 +233,67 @@ def test_bias_calibration(K, rot):
     B.basq_calibrate_bias(lay.X.to(dev), rot, None, out, ws)
     torch.cuda.synchronize()
     np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-5, atol=2e-6)
+
+
+# ---------------------------------------------------------------- group-wise ranges (per-head quantisation)
+
+def run_group_case(M, K, rot, group, *, seed=0, scale=False, bias=True, clip_lo=0.9, clip_hi=0.95, strided=False):
+    """basq_rotate_quant with group_size < K against the oracle's group-wise quantiser: codes, group records
+    and row sums bit-exact on the GPU's own rotation output; flips against the oracle's rotation rare and +-1."""
+    announce(f"group case M={M} K={K} rot={rot} group={group} scale={scale} bias={bias}")
+    lay = si.make_tiny(M, K, 8, seed=seed, n_outlier=8, outlier_scale=20.0)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    rng = np.random.default_rng(seed + 1)
+    b = oracle.channel_bias(oracle.bf16_to_f32(si.bf16_bits(lay.X_calib)), rot) if bias else None
+    sa = rng.uniform(0.8, 1.25, K).astype(np.float32) if scale else None
+    if b is not None and sa is not None:
+        b = (b.astype(np.float64) * sa).astype(np.float32)
+    dev = "cuda"
+    X = lay.X.to(dev)
+    if strided:
+        wide = torch.zeros((M, K + 64), dtype=torch.bfloat16, device=dev)
+        wide[:, :K] = X
+        X = wide[:, :K]
+    G = K // group
+    Aq = torch.zeros((M, K // 2), dtype=torch.uint8, device=dev)
+    meta = torch.zeros((M * G, 4), dtype=torch.int32, device=dev)
+    rot_out = torch.empty((M, K), dtype=torch.float32, device=dev)
+    tb = None if b is None else torch.from_numpy(b).to(dev)
+    ts = None if sa is None else torch.from_numpy(sa).to(dev)
+    B.basq_rotate_quant(X, rot, tb, ts, clip_lo, clip_hi, Aq, meta, rot_out, group_size=group)
+    Aq2 = torch.zeros_like(Aq)
+    meta2 = torch.zeros_like(meta)
+    B.basq_rotate_quant(X, rot, tb, ts, clip_lo, clip_hi, Aq2, meta2, None, group_size=group)   # no debug output: the fast variant
+    torch.cuda.synchronize()
+    assert torch.equal(Aq, Aq2) and torch.equal(meta, meta2)
+    r_gpu = rot_out.cpu().numpy()
+    ref = oracle.quantize_tokens(r_gpu, b, sa, clip_lo, clip_hi, group_size=group)
+    codes = oracle.unpack_codes(Aq.cpu().numpy())
+    mh = meta.cpu().numpy().reshape(M, G, 4)
+    np.testing.assert_array_equal(codes, ref.codes, err_msg="codes (GPU rotation fed to the oracle)")
+    np.testing.assert_array_equal(mh[:, :, 0].copy().view(np.uint32), ref.scale.view(np.uint32), err_msg="group scales")
+    np.testing.assert_array_equal(mh[:, :, 1].copy().view(np.uint32), ref.lo.view(np.uint32), err_msg="group lower bounds")
+    np.testing.assert_array_equal(mh[:, :, 2], ref.rowsum, err_msg="group code sums")
+    r_ref = oracle.rotate(x, rot)
+    assert np.abs(r_gpu - r_ref).max() <= 2e-5 * max(1.0, float(np.abs(r_ref).max()))
+    full = oracle.quantize_tokens(r_ref, b, sa, clip_lo, clip_hi, group_size=group)
+    d = codes.astype(np.int32) - full.codes.astype(np.int32)
+    assert (d != 0).mean() <= 1e-4 and (np.abs(d[d != 0]) == 1).all()
+
+
+@pytest.mark.parametrize("M,K", [(70, 4096), (33, 1024), (5, 512), (600, 2048)])
+def test_per_head_kernel(M, K):
+    """rot_size = group_size = 128: the wave-local kernel (one 512-channel item per wavefront)."""
+    run_group_case(M, K, 128, 128, seed=K + M)
+
+
+def test_per_head_kernel_variants():
+    run_group_case(40, 4096, 128, 128, seed=1, scale=True)
+    run_group_case(40, 1024, 128, 128, seed=2, bias=False, clip_lo=1.0, clip_hi=1.0)
+    run_group_case(19, 2048, 128, 128, seed=3, strided=True)
+
+
+@pytest.mark.parametrize("K,rot,group", [(1024, 64, 64), (1024, 128, 256), (768, 32, 96), (1024, 1024, 128), (28 * 64, 28 * 64, 64)])
+def test_groupwise_ranges_generic_kernel(K, rot, group):
+    """Other group sizes, groups that differ from the rotation block, and a 28 * 2^t rotation."""
+    run_group_case(37, K, rot, group, seed=K + group)
