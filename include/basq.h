@@ -42,6 +42,7 @@ extern "C" {
 #define BASQ_EHIP         (-4)  /* a HIP call or launch failed */
 
 #define BASQ_W_CANONICAL 0      /* Wq is [N, K/2] in the canonical packed layout */
+#define BASQ_W_DECODE16  1      /* Wq is in the weight-streaming layout written by basq_pack_decode */
 
 /* Per-token quantisation record written by basq_rotate_quant and read by basq_w4a4_gemm.
  * x_hat[m,k] = scale * q[m,k] + lo   (Eq. 4 with z = lo);  rowsum = sum_k q[m,k]. */
@@ -102,7 +103,9 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
  *     Y[m,n]   = bf16( s_m * sw_n * (ACC[m,n] - zp_n * rowsum_m) + lo_m * w_sum_n + out_bias_n )
  *
  *   Aq, meta   as written by basq_rotate_quant, [M, K/2] and [M]
- *   Wq         uint8 [N, K/2]; w_layout must be BASQ_W_CANONICAL
+ *   Wq         uint8 [N, K/2] with w_layout = BASQ_W_CANONICAL, or the weight-streaming layout of
+ *              basq_pack_decode with w_layout = BASQ_W_DECODE16.  The latter is read by the M <= 16 path
+ *              only: with M > 16 it needs the fp6 operands (which replace Wq), else BASQ_EUNSUPPORTED.
  *   w_scale    bf16 [N] sw;  w_zero  bf16 [N] zp in code units (any real value)
  *   w_sum      fp32 [N] = sw_n * (sum_k q_w[n,k] - K * zp_n) = sum_k W_hat[n,k]
  *   out_bias   fp32 [N] c, or NULL (= 0)
@@ -138,6 +141,22 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
  */
 size_t basq_fp6_bytes(int64_t rows, int32_t K);
 int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, void* stream);
+
+/*
+ * The weight-streaming layout for decode-sized calls (M <= 16; such a call is one pass over the weights and
+ * bound by memory bandwidth, the decode case of Sec. 5.2's speed measurement).  The matrix-core operand of
+ * that path puts 16 different rows on the 16 lanes of a quarter wavefront, so canonical weights are read in
+ * 16-byte pieces of 16 rows at a time; here the kilobyte one wavefront load consumes is contiguous instead.
+ *
+ *   Wq         device uint8 [N, K/2] canonical
+ *   out        out, device uint8, basq_decode_bytes(N, K) = ceil(N/16)*16 * K/2 bytes, 16-byte aligned.
+ *              Block nb (rows 16nb .. 16nb+15) at nb*16*K/2; inside it chunk c (bytes 64c .. 64c+63 of each
+ *              row) is the KB at c*1024; inside that, the 16-byte piece at (16*s + r)*16, s = 0..3,
+ *              r = 0..15, holds bytes 64c + 16s .. +15 of row 16nb + r.  Rows past N are zeros.
+ * K % 128 == 0.  basq_decode_bytes returns 0 for an unsupported shape.
+ */
+size_t basq_decode_bytes(int32_t N, int32_t K);
+int basq_pack_decode(const uint8_t* Wq, int32_t N, int32_t K, uint8_t* out, void* stream);
 
 /* Bytes of workspace basq_linear_fused needs for this shape (activation codes, token records, and
  * the fp6 copy of the codes). */
@@ -200,6 +219,14 @@ int basq_hadamard28(int8_t* out_host);
  * bytes to dst + m*K/2 and 16 bytes to meta + m*16.  K a multiple of 2048.  Moves tokens*(2.5K+16) bytes.
  */
 int basq_diag_stream(const void* src, void* dst, void* meta, int64_t tokens, int32_t K, void* stream);
+
+/*
+ * Read-only streaming kernel with the access pattern of the decode-sized product (M <= 16: one pass over the
+ * weights, bound by memory bandwidth): `blocks` workgroups walk `bytes` (a multiple of 32768) of src in 32 KB
+ * spans, every lane requesting eight 16-byte pieces before it consumes any; out receives blocks*256 uint32
+ * checksums.
+ */
+int basq_diag_read(const void* src, int64_t bytes, uint32_t* out, int32_t blocks, void* stream);
 
 /*
  * Register-resident int8 MFMA loop (Sec. 5.2: the prefill GEMM is compute bound): `blocks` workgroups of

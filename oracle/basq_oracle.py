@@ -201,6 +201,26 @@ def unpack_fp6(buf: np.ndarray, R: int, K: int) -> np.ndarray:
     return out
 
 
+def pack_decode16(p: np.ndarray) -> np.ndarray:
+    """[N, K/2] canonical packed weight bytes, K % 128 == 0 -> the weight-streaming layout of the decode
+    path, a flat uint8 array of ceil(N/16)*16 * K/2 bytes.  It is a pure permutation of 16-byte pieces:
+    block nb (rows 16nb..16nb+15) at nb*16*K/2; chunk c (bytes 64c..64c+63 of every row) is the KB at
+    c*1024 inside the block; piece (s, r) at (16s + r)*16 holds bytes 64c+16s .. +15 of row 16nb + r.
+    Rows past N are zeros."""
+    assert p.dtype == np.uint8 and p.ndim == 2 and p.shape[1] % 64 == 0
+    N, KB = p.shape
+    NB = (N + 15) // 16
+    out = np.zeros(NB * 16 * KB, dtype=np.uint8)
+    for n in range(N):
+        nb, r = divmod(n, 16)
+        for c in range(KB // 64):
+            for s_ in range(4):
+                dst = nb * 16 * KB + c * 1024 + (16 * s_ + r) * 16
+                out[dst:dst + 16] = p[n, 64 * c + 16 * s_: 64 * c + 16 * s_ + 16]
+    return out
+
+
+
 # ------------------------------------------------------------------------------------------------
 # Hadamard matrices (Sec. 3.1: orthogonal Hadamard rotation, entries +-n^(-1/2))
 # ------------------------------------------------------------------------------------------------

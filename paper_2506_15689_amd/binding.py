@@ -18,10 +18,11 @@ BASQ_EUNSUPPORTED = -2
 BASQ_EWORKSPACE = -3
 BASQ_EHIP = -4
 BASQ_W_CANONICAL = 0
+BASQ_W_DECODE16 = 1
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
-           "basq_fp6_bytes", "basq_pack_fp6", "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
-           "basq_hadamard28", "basq_diag_stream", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
+           "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_hadamard28", "basq_diag_stream", "basq_diag_read", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
 class BasqError(RuntimeError):
@@ -56,6 +57,10 @@ def load() -> ctypes.CDLL:
     lib.basq_fp6_bytes.argtypes = [i64, i32]
     lib.basq_pack_fp6.restype = c.c_int
     lib.basq_pack_fp6.argtypes = [vp, i64, i32, vp, vp]
+    lib.basq_decode_bytes.restype = c.c_size_t
+    lib.basq_decode_bytes.argtypes = [i32, i32]
+    lib.basq_pack_decode.restype = c.c_int
+    lib.basq_pack_decode.argtypes = [vp, i32, i32, vp, vp]
     lib.basq_workspace_bytes.restype = c.c_size_t
     lib.basq_workspace_bytes.argtypes = [i64, i32, i32]
     lib.basq_linear_fused.restype = c.c_int
@@ -71,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.basq_hadamard28.argtypes = [vp]
     lib.basq_diag_stream.restype = c.c_int
     lib.basq_diag_stream.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.basq_diag_read.restype = c.c_int
+    lib.basq_diag_read.argtypes = [vp, i64, vp, i32, vp]
     lib.basq_diag_mfma_i8.restype = c.c_int
     lib.basq_diag_mfma_i8.argtypes = [vp, i32, i32, vp]
     lib.basq_diag_mfma_f6.restype = c.c_int
@@ -127,9 +134,11 @@ def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_sca
                    w_zero: torch.Tensor, w_sum: torch.Tensor, out_bias: Optional[torch.Tensor], Y: torch.Tensor,
                    acc_out: Optional[torch.Tensor] = None, *, Aq6: Optional[torch.Tensor] = None,
                    Wq6: Optional[torch.Tensor] = None,
-                   w_layout: int = BASQ_W_CANONICAL, stream: Optional[torch.cuda.Stream] = None) -> None:
+                   w_layout: int = BASQ_W_CANONICAL, N: Optional[int] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> None:
+    """N defaults to Wq.shape[0]; give it when Wq is a flat buffer in the streaming layout."""
     M, KB = Aq.shape
-    N = Wq.shape[0]
+    N = Wq.shape[0] if N is None else N
     _check(load().basq_w4a4_gemm(_p(Aq), _p(meta), M, KB * 2, _p(Wq), N, w_layout, _p(w_scale), _p(w_zero),
                                  _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _p(acc_out),
                                  _p(Aq6), _p(Wq6), _stream(stream)))
@@ -145,15 +154,25 @@ def basq_pack_fp6(codes: torch.Tensor, out6: torch.Tensor, *, stream: Optional[t
     _check(load().basq_pack_fp6(_p(codes), rows, KB * 2, _p(out6), _stream(stream)))
 
 
+def basq_decode_bytes(N: int, K: int) -> int:
+    return int(load().basq_decode_bytes(N, K))
+
+
+def basq_pack_decode(Wq: torch.Tensor, out: torch.Tensor, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Wq uint8 [N, K/2] canonical -> out uint8 [basq_decode_bytes(N, K)] (weight-streaming layout)."""
+    N, KB = Wq.shape
+    _check(load().basq_pack_decode(_p(Wq), N, KB * 2, _p(out), _stream(stream)))
+
+
 def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tensor],
                       act_scale: Optional[torch.Tensor], clip_lo: float, clip_hi: float, Wq: torch.Tensor,
                       w_scale: torch.Tensor, w_zero: torch.Tensor, w_sum: torch.Tensor,
                       out_bias: Optional[torch.Tensor], Y: torch.Tensor, workspace: torch.Tensor, *,
                       Wq6: Optional[torch.Tensor] = None,
                       bits: int = 4, group_size: int = 0, w_layout: int = BASQ_W_CANONICAL,
-                      stream: Optional[torch.cuda.Stream] = None) -> None:
+                      N: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
     M, K = X.shape
-    N = Wq.shape[0]
+    N = Wq.shape[0] if N is None else N
     _check(load().basq_linear_fused(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
                                     clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout, _p(w_scale),
                                     _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
@@ -187,6 +206,11 @@ def basq_calibrate_bias(X: torch.Tensor, rot_size: int, act_scale: Optional[torc
 def basq_diag_stream(src: torch.Tensor, dst: torch.Tensor, meta: torch.Tensor, tokens: int, K: int, *,
                      stream: Optional[torch.cuda.Stream] = None) -> None:
     _check(load().basq_diag_stream(_p(src), _p(dst), _p(meta), tokens, K, _stream(stream)))
+
+
+def basq_diag_read(src: torch.Tensor, out: torch.Tensor, blocks: int, *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """src: any tensor of a multiple of 32768 bytes; out int32/uint32 [blocks*256]."""
+    _check(load().basq_diag_read(_p(src), src.numel() * src.element_size(), _p(out), blocks, _stream(stream)))
 
 
 def basq_diag_mfma_i8(out: torch.Tensor, blocks: int, iters: int, *, stream: Optional[torch.cuda.Stream] = None) -> None:

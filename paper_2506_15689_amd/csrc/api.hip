@@ -61,7 +61,10 @@ int validate_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_
     if (M < 0) return fail(BASQ_EINVAL, "M must be >= 0 (got %lld)", (long long)M);
     if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
     if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
-    if (w_layout != BASQ_W_CANONICAL) return fail(BASQ_EUNSUPPORTED, "unknown w_layout %d", w_layout);
+    if (w_layout != BASQ_W_CANONICAL && w_layout != BASQ_W_DECODE16)
+        return fail(BASQ_EUNSUPPORTED, "unknown w_layout %d", w_layout);
+    if (w_layout == BASQ_W_DECODE16 && K % 128 != 0)
+        return fail(BASQ_EINVAL, "the streaming weight layout needs K %% 128 == 0 (got %d)", K);
     if (ldy < N) return fail(BASQ_EINVAL, "ldy must be >= N (got %lld)", (long long)ldy);
     if (!Wq || !w_scale || !w_zero || !w_sum) return fail(BASQ_EINVAL, "a weight-side pointer is null");
     if (M > 0 && (!Aq || !meta || !Y)) return fail(BASQ_EINVAL, "an activation-side pointer is null");
@@ -75,6 +78,9 @@ int validate_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_
 int run_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 16 && g.K % 128 == 0) return launch_gemv_decode(g, s);
     if (gemm_fp6_applicable(g)) return launch_gemm_fp6(g, s);
+    if (g.w_layout != BASQ_W_CANONICAL)
+        return fail(BASQ_EUNSUPPORTED, "more than 16 tokens with the streaming weight layout need the fp6 operands "
+                                        "(the int8 kernels read canonical weights)");
     return launch_gemm_prefill(g, s);
 }
 
@@ -131,7 +137,7 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
     rc = validate_fp6(Aq6, Wq6, true, K);
     if (rc != BASQ_OK) return rc;
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, acc_out, Aq6, Wq6};
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, acc_out, Aq6, Wq6, w_layout};
     return run_gemm(g, static_cast<hipStream_t>(stream));
 }
 
@@ -153,6 +159,19 @@ int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, 
     if (rows > 0 && (!codes || !out6)) return fail(BASQ_EINVAL, "codes or out6 is null");
     if (!aligned16(codes) || !aligned16(out6)) return fail(BASQ_EINVAL, "codes and out6 must be 16-byte aligned");
     return launch_pack_fp6(codes, rows, K, out6, static_cast<hipStream_t>(stream));
+}
+
+size_t basq_decode_bytes(int32_t N, int32_t K) {
+    if (N <= 0 || K <= 0 || K % 128 != 0) return 0;
+    return (size_t)((N + 15) / 16 * 16) * (size_t)(K / 2);
+}
+
+int basq_pack_decode(const uint8_t* Wq, int32_t N, int32_t K, uint8_t* out, void* stream) {
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (K <= 0 || K % 128 != 0) return fail(BASQ_EINVAL, "the streaming weight layout needs K to be a positive multiple of 128 (got %d)", K);
+    if (!Wq || !out) return fail(BASQ_EINVAL, "Wq or out is null");
+    if (!aligned16(Wq) || !aligned16(out)) return fail(BASQ_EINVAL, "Wq and out must be 16-byte aligned");
+    return launch_pack_decode16(Wq, N, K, out, static_cast<hipStream_t>(stream));
 }
 
 int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
@@ -191,10 +210,13 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     a.group = K;
     a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, w_layout};
+    if (w_layout != BASQ_W_CANONICAL && M > 16 && !gemm_fp6_applicable(g))      // before anything is launched
+        return fail(BASQ_EUNSUPPORTED, "more than 16 tokens with the streaming weight layout need the fp6 operands "
+                                        "(the int8 kernels read canonical weights)");
     rc = launch_rotate_quant(a, s);
     if (rc != BASQ_OK) return rc;
-    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr};
     return run_gemm(g, s);
 }
 

@@ -59,12 +59,14 @@ struct GemmArgs {
     // fp6 operand form of both matrices; both or neither (gemm_w4a4_fp6.hip)
     const uint8_t* Aq6;
     const uint8_t* Wq6;
+    int32_t w_layout;         // layout of Wq: BASQ_W_CANONICAL, or BASQ_W_DECODE16 (read by the M <= 16 kernel only)
 };
 int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 // direct-to-LDS kernel for K % 256 == 0 (gemm_w4a4_direct.hip)
 bool gemm_direct_applicable(const GemmArgs& a);
 int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
+int launch_pack_decode16(const uint8_t* Wq, int32_t N, int32_t K, uint8_t* out, hipStream_t s);
 // f8f6f4 MFMA kernel on the fp6 operand form, K % 128 == 0 (gemm_w4a4_fp6.hip)
 bool gemm_fp6_applicable(const GemmArgs& a);
 int launch_gemm_fp6(const GemmArgs& a, hipStream_t s);

@@ -1,7 +1,9 @@
-// Two diagnostic kernels that measure what this machine sustains, so that the benchmark can report
+// Diagnostic kernels that measure what this machine sustains, so that the benchmark can report
 // each hot kernel against a measured ceiling next to the published peak:
 //   basq_diag_stream   a pure streaming kernel with the rotate+quant kernel's access pattern
 //                      (one wave per token, 2K bytes in, K/2 + 16 bytes out, non-temporal)
+//   basq_diag_read     a read-only streaming kernel with the decode kernel's access pattern (a workgroup
+//                      requests 32 KB, eight 16-byte non-temporal loads per lane, before it consumes any)
 //   basq_diag_mfma_i8  a register-resident v_mfma_i32_32x32x32_i8 loop, 4-bit valued operands
 //   basq_diag_mfma_f6  the same with v_mfma_f32_32x32x64_f8f6f4 on fp6 (e2m3) operands that encode 4-bit codes
 // Neither computes anything of the method.
@@ -30,6 +32,19 @@ __global__ __launch_bounds__(256) void diag_stream_kernel(const uint8_t* src, ui
         for (int c = 0; c < nstore; ++c) nt_store16(y + c * 1024, acc);
         if (lane == 0) *reinterpret_cast<uint4*>(meta + m * 16) = acc;
     }
+}
+
+__global__ __launch_bounds__(256) void diag_read_kernel(const uint8_t* src, int64_t spans, uint32_t* out) {
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (int64_t sp = blockIdx.x; sp < spans; sp += gridDim.x) {
+        const uint8_t* p = src + sp * 32768 + threadIdx.x * 16;
+        uint4 r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = nt_load16(p + i * 4096);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { acc.x ^= r[i].x; acc.y += r[i].y; acc.z ^= r[i].z; acc.w += r[i].w; }
+    }
+    out[blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
 }
 
 __global__ __launch_bounds__(256) void diag_mfma_kernel(int* out, int iters) {
@@ -111,6 +126,15 @@ int basq_diag_stream(const void* src, void* dst, void* meta, int64_t tokens, int
     hipLaunchKernelGGL(diag_stream_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst), static_cast<uint8_t*>(meta), tokens, K);
     return check_hip(hipGetLastError(), "diag_stream launch");
+}
+
+int basq_diag_read(const void* src, int64_t bytes, uint32_t* out, int32_t blocks, void* stream) {
+    if (!src || !out) return fail(BASQ_EINVAL, "diag_read: a pointer is null");
+    if (bytes < 32768 || bytes % 32768 != 0 || blocks < 1 || blocks > 65536)
+        return fail(BASQ_EINVAL, "diag_read: bytes must be a positive multiple of 32768, blocks in 1..65536");
+    hipLaunchKernelGGL(diag_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t*>(src), bytes / 32768, out);
+    return check_hip(hipGetLastError(), "diag_read launch");
 }
 
 int basq_diag_mfma_i8(int32_t* out, int32_t blocks, int32_t iters, void* stream) {

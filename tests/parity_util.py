@@ -99,6 +99,11 @@ class GpuResult:
     acc6: Optional[np.ndarray] = None
     y6_bits: Optional[np.ndarray] = None
     y6_fused_bits: Optional[np.ndarray] = None
+    # the same layer with the weights in the weight-streaming layout (None when K % 128 != 0)
+    wd: Optional[np.ndarray] = None          # the layout as written by pack_decode
+    accd: Optional[np.ndarray] = None        # decode-sized M only: the int32 accumulators of that path
+    yd_bits: Optional[np.ndarray] = None
+    yd_fused_bits: Optional[np.ndarray] = None
 
 
 def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
@@ -136,6 +141,22 @@ def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
         assert torch.equal(Aq2, Aq) and torch.equal(meta2, meta), "rotate_quant with and without the fp6 output"
         res.a6, res.w6 = A6.cpu().numpy(), W6.cpu().numpy()
         res.acc6, res.y6_bits, res.y6_fused_bits = acc6.cpu().numpy(), si.bf16_bits(Y6.cpu()), si.bf16_bits(Y6f.cpu())
+        # third pass: weights in the streaming layout (read by the M <= 16 kernel; larger M runs on the fp6
+        # operands and must not touch Wq at all)
+        Wd = torch.empty(B.basq_decode_bytes(N, K), dtype=torch.uint8, device=dev).fill_(0xEE)
+        B.basq_pack_decode(d.Wq, Wd)
+        Yd = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+        Ydf = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
+        accd = torch.full((M, N), -1, dtype=torch.int32, device=dev)
+        fp6 = dict(Aq6=A6, Wq6=W6) if M > 16 else {}
+        B.basq_w4a4_gemm(Aq, meta, Wd, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Yd, accd,
+                         w_layout=B.BASQ_W_DECODE16, N=N, **fp6)
+        B.basq_linear_fused(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, Wd, d.w_scale,
+                            d.w_zero, d.w_sum, d.out_bias, Ydf, ws, w_layout=B.BASQ_W_DECODE16, N=N,
+                            Wq6=W6 if M > 16 else None)
+        torch.cuda.synchronize()
+        res.wd, res.accd = Wd.cpu().numpy(), accd.cpu().numpy()
+        res.yd_bits, res.yd_fused_bits = si.bf16_bits(Yd.cpu()), si.bf16_bits(Ydf.cpu())
     return res
 
 
@@ -168,6 +189,24 @@ def check_fp6_path(case: Case, g: GpuResult, *, row_blocks: Optional[np.ndarray]
                 mask = oracle.pack_fp6(np.full((n, K), 15, dtype=np.uint8)).reshape(K // 128, 3072) != 0
                 mask |= oracle.pack_fp6(np.full((n, K), 1, dtype=np.uint8)).reshape(K // 128, 3072) != 0
                 np.testing.assert_array_equal(got[:, rb][mask], ref[mask], err_msg=f"fp6 form of the {name}, last block")
+
+
+def check_decode_layout(case: Case, g: GpuResult) -> None:
+    """Weights in the streaming layout: the buffer is the oracle's permutation of the canonical bytes, and
+    the layer gives the bits of the canonical-layout run (which check_parity ties to the oracle)."""
+    if g.wd is None:
+        return
+    N, K = case.wq.codes.shape
+    KB = K // 2
+    NB = (N + 15) // 16
+    blocks = np.arange(NB) if N * K <= (1 << 22) else np.unique([0, NB // 2, NB - 1])
+    canon = oracle.pack_codes(case.wq.codes)
+    for nb in blocks:                               # the layout is independent per 16-row block
+        ref = oracle.pack_decode16(np.ascontiguousarray(canon[16 * nb:16 * nb + 16]))
+        np.testing.assert_array_equal(g.wd[nb * 16 * KB:(nb + 1) * 16 * KB], ref, err_msg=f"streaming layout, block {nb}")
+    np.testing.assert_array_equal(g.accd, g.acc, err_msg="INT32 accumulators, streaming layout vs canonical")
+    np.testing.assert_array_equal(g.yd_bits, g.y_bits, err_msg="outputs, streaming layout vs canonical")
+    np.testing.assert_array_equal(g.yd_fused_bits, g.y_bits, err_msg="basq_linear_fused, streaming layout")
 
 
 def check_parity(case: Case, g: GpuResult, *, rows: Optional[np.ndarray] = None, use_blas_gemm: bool = False,

@@ -104,6 +104,29 @@ def run_fullsize(name, n_rows, n_cols, M=None):
                 np.testing.assert_array_equal(got[:, rb].cpu().numpy(), ref6, err_msg=f"fp6 form of the {name6}, block {rb}")
         del Wq6, Aq6, Aq2, meta2, acc6, Y6, Y6f
 
+    # ---- a decode-sized call (the first 16 tokens) on the whole weight matrix in the streaming layout: the
+    # bits of the canonical-layout call, which in turn equal the rows of the full product checked below
+    if K % 128 == 0:
+        Wd = torch.empty(B.basq_decode_bytes(N, K), dtype=torch.uint8, device=dev)
+        B.basq_pack_decode(Wq, Wd)
+        m16 = min(M, 16)
+        accc = torch.empty((m16, N), dtype=torch.int32, device=dev)
+        accd = torch.empty((m16, N), dtype=torch.int32, device=dev)
+        Yc = torch.empty((m16, N), dtype=torch.bfloat16, device=dev)
+        Yd = torch.empty((m16, N), dtype=torch.bfloat16, device=dev)
+        B.basq_w4a4_gemm(Aq[:m16], meta[:m16], Wq, w_scale, w_zero, w_sum, out_bias, Yc, accc)
+        B.basq_w4a4_gemm(Aq[:m16], meta[:m16], Wd, w_scale, w_zero, w_sum, out_bias, Yd, accd,
+                         w_layout=B.BASQ_W_DECODE16, N=N)
+        torch.cuda.synchronize()
+        assert torch.equal(accc, acc[:m16]), "decode path differs from the prefill path on the same tokens"
+        assert torch.equal(accd, accc) and torch.equal(Yd, Yc), "streaming layout differs from canonical"
+        KB, NB = K // 2, (N + 15) // 16
+        for nb in sorted({0, NB // 2, NB - 1}):
+            refd = oracle.pack_decode16(Wq[16 * nb:16 * nb + 16].cpu().numpy())
+            np.testing.assert_array_equal(Wd[nb * 16 * KB:(nb + 1) * 16 * KB].cpu().numpy(), refd,
+                                          err_msg=f"streaming layout, block {nb}")
+        del Wd, accc, accd, Yc, Yd
+
     t_rows = torch.from_numpy(rows).to(dev)
     t_cols = torch.from_numpy(cols).to(dev)
     # weights of the sampled channels: bit-exact

@@ -30,6 +30,7 @@ def run_case(lay, **kw):
     g = pu.run_gpu(case, d)
     stats = pu.check_parity(case, g, rows=rows, use_blas_gemm=blas)
     pu.check_fp6_path(case, g)
+    pu.check_decode_layout(case, g)
     announce(f"ok {stats}")
     return stats
 
@@ -100,6 +101,13 @@ def test_decode_shapes_full(name):
 @pytest.mark.parametrize("M,K,N", [(1, 1024, 24), (3, 512, 16), (16, 256, 100), (5, 96, 33)])
 def test_decode_ragged(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=3 * M + N), rot_size=K if K != 96 else 32)
+
+
+@pytest.mark.parametrize("M,N", [(16, 16392), (9, 16400), (8, 16392)])
+def test_decode_many_output_channels(M, N):
+    """More than 1024 blocks of 16 output channels: with more than 8 tokens a workgroup takes two blocks
+    (an odd number of blocks and a ragged last block here); with 8 tokens it takes one."""
+    run_case(si.make_tiny(M, 128, N, seed=M + N), use_blas_gemm=True)
 
 
 # ---------------------------------------------------------------- edge cases

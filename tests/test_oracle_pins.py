@@ -519,3 +519,23 @@ def test_fp6_layout_round_trip_and_placement():
     b2 = oracle.pack_fp6(one)
     t = 2048 + 256 * 0 + 8 * 2 + 6
     assert np.flatnonzero(b2).tolist() == [t] and b2[t] == (0b001111 << 4) & 0xFF
+
+
+def test_decode_layout_is_the_stated_permutation():
+    """The weight-streaming layout only moves 16-byte pieces.  Checked three ways: one byte placed by hand,
+    the multiset of bytes, and the layout read back as an axis transposition [block, chunk, s, r, 16] ->
+    [block, r, chunk, s, 16] (the walk in the oracle is loops over rows, chunks and pieces)."""
+    rng = np.random.default_rng(11)
+    p = rng.integers(0, 256, (40, 192), dtype=np.uint8)                    # 40 rows: a ragged third block; K = 384
+    buf = oracle.pack_decode16(p)
+    assert buf.shape == (48 * 192,)
+    back = buf.reshape(3, 3, 4, 16, 16).transpose(0, 3, 1, 2, 4).reshape(48, 192)
+    np.testing.assert_array_equal(back[:40], p)
+    assert not back[40:].any()
+    np.testing.assert_array_equal(np.sort(buf)[-p.size:], np.sort(p.ravel()))
+    # row 21 (block 1, r = 5), byte 150 of the row = chunk 2, s = 1, byte 6 of the piece
+    one = np.zeros((40, 192), dtype=np.uint8)
+    one[21, 150] = 0xA7
+    b = oracle.pack_decode16(one)
+    where = 1 * 16 * 192 + 2 * 1024 + (16 * 1 + 5) * 16 + 6
+    assert np.flatnonzero(b).tolist() == [where] and b[where] == 0xA7
