@@ -345,6 +345,8 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": rot_size, "group_size": group if group else K,
                    "clip": cfg.clip, "buffer_sets": nsets, "weight_copies": len(wsets),
                    "weight_layout": "streaming (16-row blocks)" if w_layout == B.BASQ_W_DECODE16 else "canonical",
+                   "step_launches": 1 if (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192)
+                                          and rot_size == K) else 2,
                    "matrix_path": "fp6" if use_fp6 else ("int8" if M > 16 else "int4 weight streaming")},
         "rotate_quant_GBps": rq_gbs,
         "roofline": roof_rq if rq_only else roof,

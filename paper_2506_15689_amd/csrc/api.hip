@@ -215,6 +215,7 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     if (w_layout != BASQ_W_CANONICAL && M > 16 && !gemm_fp6_applicable(g))      // before anything is launched
         return fail(BASQ_EUNSUPPORTED, "more than 16 tokens with the streaming weight layout need the fp6 operands "
                                         "(the int8 kernels read canonical weights)");
+    if (linear_decode_applicable(a, g)) return launch_linear_decode(a, g, s);      // a few tokens: one launch
     rc = launch_rotate_quant(a, s);
     if (rc != BASQ_OK) return rc;
     return run_gemm(g, s);

@@ -66,6 +66,9 @@ int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 bool gemm_direct_applicable(const GemmArgs& a);
 int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
+// one launch for the whole layer at decode size (linear_decode.hip)
+bool linear_decode_applicable(const RotateQuantArgs& q, const GemmArgs& g);
+int launch_linear_decode(const RotateQuantArgs& q, const GemmArgs& g, hipStream_t s);
 int launch_pack_decode16(const uint8_t* Wq, int32_t N, int32_t K, uint8_t* out, hipStream_t s);
 // f8f6f4 MFMA kernel on the fp6 operand form, K % 128 == 0 (gemm_w4a4_fp6.hip)
 bool gemm_fp6_applicable(const GemmArgs& a);

@@ -1,34 +1,11 @@
 // Fast rotate + bias + quantise kernel for rot_size == K in {4096, 8192}: one wavefront per token,
-// the token never leaves registers except for one wave-private LDS transpose.
-// (Paper Sec. 5.2 applies the online Hadamard as matrix products on the matrix cores instead of a
-// pure butterfly recursion; here the first five stages are one bf16 MFMA -- exact, since the inputs
-// are bf16 and the matrix entries are +-2^-6 or +-1 -- and the remaining stages are fp32
-// butterflies in registers.)
-//
-// Channel index e (12 bits for K = 4096; bit 12 for K = 8192 rides along in registers).
-//   load      lane l reads 8 consecutive bf16 (16 B); 8 (16) loads of 1 KB each per token.
-//             e = 512*c + 8*chunk(l) + t,  chunk bits (e3..e8) <- lane bits (2,3,0,1,4,5)
-//   MFMA      D = A.B, A = the 16 x 32 slice of the token (row = l%16, k = 8*(l/16) + t), B = H_32
-//             over the index bits (e0,e1,e2,e7,e8), columns permuted so that output bit e0 lands
-//             in the half index h and (e1,e2,e7,e8) in output lane bits 0..3.
-//             After it a lane holds d[c][h][r]: e0 = h, (e5,e6) = r, (e9..) = c,
-//             lane bits (0,1,2,3,4,5) = (e1,e2,e7,e8,e3,e4).
-//   stages    e5, e6, e9, e10, e11 (, e12) in registers.
-//   transpose through LDS (8 KB per wave, reused per 2048 channels, 8-byte accesses, no bank conflicts) to the layout
-//             lane bits (0..5) = (e5..e10), registers = (e0..e4, e11 (, e12)).
-//   stages    e3, e4 in registers.
-//   now a lane owns 32 consecutive channels (x2 or x4): bias, min/max, quantise, pack, 16-byte stores.
-#include "basq_internal.h"
+// the token never leaves registers except for one wave-private LDS transpose (the per-token routine and
+// its layout notes are in rotate_pow2_token.h; paper Sec. 3.1 rotation, Eq. 14 bias, Eq. 4 quantiser).
+#include "rotate_pow2_token.h"
 
 namespace basq {
 
 namespace {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef int v6i __attribute__((ext_vector_type(6)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef short v8s __attribute__((ext_vector_type(8)));
 
 #ifndef P2_WAVES_CFG
 #define P2_WAVES_CFG 4
@@ -41,103 +18,23 @@ constexpr int P2_THREADS = P2_WAVES * 64;
 #ifndef P2_PREFETCH
 #define P2_PREFETCH 1
 #endif
-constexpr int P2_LDS_WORDS = 2048;          // per wave
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-template <int CTRL>
-__device__ __forceinline__ int dpp_i(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
-}
-constexpr int DPP_QUAD_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
-constexpr int DPP_QUAD_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
-constexpr int DPP_ROW_HALF_MIRROR = 0x141;
-constexpr int DPP_ROW_MIRROR = 0x140;
-
-__device__ __forceinline__ float wave_min_f(float v) {
-    v = fminf(v, dpp_f<DPP_QUAD_XOR1>(v));
-    v = fminf(v, dpp_f<DPP_QUAD_XOR2>(v));
-    v = fminf(v, dpp_f<DPP_ROW_HALF_MIRROR>(v));
-    v = fminf(v, dpp_f<DPP_ROW_MIRROR>(v));
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return fminf(fminf(r0, r1), fminf(r2, r3));
-}
-__device__ __forceinline__ float wave_max_f(float v) {
-    v = fmaxf(v, dpp_f<DPP_QUAD_XOR1>(v));
-    v = fmaxf(v, dpp_f<DPP_QUAD_XOR2>(v));
-    v = fmaxf(v, dpp_f<DPP_ROW_HALF_MIRROR>(v));
-    v = fmaxf(v, dpp_f<DPP_ROW_MIRROR>(v));
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-__device__ __forceinline__ int wave_sum_i(int v) {
-    v += dpp_i<DPP_QUAD_XOR1>(v);
-    v += dpp_i<DPP_QUAD_XOR2>(v);
-    v += dpp_i<DPP_ROW_HALF_MIRROR>(v);
-    v += dpp_i<DPP_ROW_MIRROR>(v);
-    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-           __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
-}
-
-#define BFLY(x, y) do { const float _a = (x), _b = (y); (x) = _a + _b; (y) = _a - _b; } while (0)
 
 // NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
 // sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
 template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
 __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
     constexpr int K = 512 * NC;
-    constexpr int NH = NC / 8;                  // number of 4096-channel halves (bit 12)
     constexpr bool PREFETCH = (NC == 8) && P2_PREFETCH;
-    static_assert(NC == 8 || NC == 16, "K must be 4096 or 8192");
-    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves) laid out so
-    // that lane l's i-th 16-byte piece sits at float4 index (piece group)*64 + l: conflict-free reads
+    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves)
     constexpr int BIAS_WORDS = HAS_BIAS ? K : 0;
     __shared__ __attribute__((aligned(16))) float lds[P2_WAVES * P2_LDS_WORDS + BIAS_WORDS];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* wl = lds + wave * P2_LDS_WORDS;
     const float4* lbias = reinterpret_cast<const float4*>(lds + P2_WAVES * P2_LDS_WORDS);
-    if (HAS_BIAS) {
-        float4* dst = reinterpret_cast<float4*>(lds + P2_WAVES * P2_LDS_WORDS);
-        for (int f = threadIdx.x; f < K / 4; f += P2_THREADS) {
-            const int e = 4 * f;                          // channels e .. e+3 belong to lane (e%2048)/32, piece (e%32)/4
-            dst[((e >> 11) * 8 + ((e & 31) >> 2)) * 64 + ((e & 2047) >> 5)] = *reinterpret_cast<const float4*>(a.bias + e);
-        }
-        __syncthreads();
-    }
-
-    // ---- constants of this lane -------------------------------------------------------------
-    // B operand: column j' = lane%16 of half h, k = 8*(lane/16) + t; input index bits (t0,t1,t2,g0,g1),
-    // output index bits (h, j'0, j'1, j'2, j'3): sign = parity(popcount(kin & jout)).
     v8bf bop[2];
-    {
-        const int jp = lane & 15, g = lane >> 4;
-        const uint16_t mag = FOLD_NORM ? (uint16_t)(((127 - (NC == 8 ? 6 : 0)) << 7)) : (uint16_t)0x3F80;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            v8s tmp;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int kin = t | (g << 3), jout = h | (jp << 1);
-                tmp[t] = (short)(mag | ((__builtin_popcount(kin & jout) & 1) ? 0x8000 : 0));
-            }
-            bop[h] = __builtin_bit_cast(v8bf, tmp);
-        }
-    }
-    // global load: chunk bits (e3,e4,e5,e6,e7,e8) <- lane bits (2,3,0,1,4,5)
-    const int chunk = ((lane >> 2) & 3) | ((lane & 3) << 2) | (lane & 0x30);
-    // LDS write base (words), lane bits (0..5) = (e1,e2,e7,e8,e3,e4); address map at the transpose below
-    const int wbase = ((lane & 15) << 1) | (((lane >> 4) & 3) << 7);
-    // LDS read base: lane bits (0..5) = (e5..e10)
-    const int rbase = ((lane & 15) << 1) | ((lane & 3) << 5) | (((lane >> 4) & 3) << 9);
+    p2_make_bop<NC, FOLD_NORM>(lane, bop);
+    const P2Lane pl = p2_lane(lane);
 
     // Workgroups g, g+8, g+16, ... run on one XCD.  Renumbering them so that an XCD owns a contiguous
     // range makes 32 consecutive tokens (one block of the fp6 output) meet in one L2, where their 8- and
@@ -150,158 +47,29 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
 
     uint4 raw[NC];
     auto load_token = [&](int64_t m) {
-        const uint16_t* x = a.X + m * a.ldx + 8 * chunk;
+        const uint16_t* x = a.X + m * a.ldx + 8 * pl.chunk;
 #pragma unroll
         for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
     };
 
+    // K = 4096: the first token is requested before the bias is staged, so that the two latencies overlap
+    // (K = 8192 has no registers to carry a token across the loop edge)
     int64_t m = wave_id;
     if (PREFETCH && m < a.M) load_token(m);
+    if (HAS_BIAS) {
+        p2_stage_bias<K>(lds + P2_WAVES * P2_LDS_WORDS, a.bias, threadIdx.x, P2_THREADS);
+        __syncthreads();
+    }
+
     for (; m < a.M; m += wave_stride) {
         if (!PREFETCH) load_token(m);
-        // ---- first five stages on the matrix core ---------------------------------------------
-        float d[NC][2][4];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const v8bf aop = __builtin_bit_cast(v8bf, raw[c]);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                v4f acc = {0.f, 0.f, 0.f, 0.f};
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[h], acc, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) d[c][h][r] = acc[r];
-            }
-        }
-        // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
         const int64_t mnext = m + wave_stride;
-        if (PREFETCH && mnext < a.M) load_token(mnext);
-
-        // ---- stages e5, e6 (r bits) and e9.. (c bits) --------------------------------------------
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                BFLY(d[c][h][0], d[c][h][1]);
-                BFLY(d[c][h][2], d[c][h][3]);
-                BFLY(d[c][h][0], d[c][h][2]);
-                BFLY(d[c][h][1], d[c][h][3]);
-            }
-#pragma unroll
-        for (int s = 1; s < NC; s <<= 1)
-#pragma unroll
-            for (int c = 0; c < NC; ++c)
-                if ((c & s) == 0)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) BFLY(d[c][h][r], d[c + s][h][r]);
-
-        // ---- transpose through LDS, 2048 channels (one value of e11, e12) at a time ---------------------
-        // word address bits: [0] = e0, [2:1] = (e1^e5, e2^e6), [4:3] = (e7,e8), [6:5] = (e5,e6),
-        //                    [8:7] = (e3,e4), [10:9] = (e9,e10)
-        // p[half][e11][idx], idx = e0..e4
-        float p[NH][2][32];
-#pragma unroll
-        for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int c01 = 0; c01 < 4; ++c01) {
-                        const int r0 = r & 1, r1 = r >> 1;
-                        const int addr = (wbase ^ ((r0 << 1) | (r1 << 2))) | (r0 << 5) | (r1 << 6) | (c01 << 9);
-                        const int c = 8 * hf + 4 * c2 + c01;
-                        *reinterpret_cast<float2*>(wl + addr) = make_float2(d[c][0][r], d[c][1][r]);
-                    }
-                // LDS serves one wave's instructions in issue order: the reads below see these writes,
-                // and the next round's writes do not overtake these reads
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    const int e1 = q & 1, e2 = (q >> 1) & 1, e3 = (q >> 2) & 1, e4 = q >> 3;
-                    const int addr = (rbase ^ ((e1 << 1) | (e2 << 2))) | (e3 << 7) | (e4 << 8);
-                    const float2 v = *reinterpret_cast<const float2*>(wl + addr);
-                    const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
-                    p[hf][c2][idx] = v.x;
-                    p[hf][c2][idx | 1] = v.y;
-                }
-                __builtin_amdgcn_wave_barrier();
-            }
-
-        // ---- stages e3, e4 ----------------------------------------------------------------------
-#pragma unroll
-        for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-#pragma unroll
-                for (int i = 0; i < 32; ++i) if ((i & 8) == 0) BFLY(p[hf][b][i], p[hf][b][i | 8]);
-#pragma unroll
-                for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[hf][b][i], p[hf][b][i | 16]);
-            }
-        // ---- normalise, bias, min/max ---------------------------------------------------------------
-        // this lane owns channels e = 4096*hf + 2048*b + 32*lane + i
-        float mn = INFINITY, mx = -INFINITY;
-#pragma unroll
-        for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int e0 = 4096 * hf + 2048 * b + 32 * lane;
-#pragma unroll
-                for (int i4 = 0; i4 < 8; ++i4) {
-                    float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
-                    if (HAS_BIAS) bb = lbias[((2 * hf + b) * 8 + i4) * 64 + lane];
-                    if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(a.act_scale + e0 + 4 * i4);
-                    const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
-                    const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
-                    float rr[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float r = p[hf][b][4 * i4 + j];
-                        if (!FOLD_NORM) r = r * norm;
-                        rr[j] = r;
-                        const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
-                        p[hf][b][4 * i4 + j] = v;
-                        mn = fminf(mn, v);
-                        mx = fmaxf(mx, v);
-                    }
-                    if (ROT_OUT)
-                        *reinterpret_cast<float4*>(a.rot_out + m * (int64_t)K + e0 + 4 * i4) =
-                            make_float4(rr[0], rr[1], rr[2], rr[3]);
-                }
-            }
-        mn = wave_min_f(mn);
-        mx = wave_max_f(mx);
-
-        const float lo = a.clip_lo * mn;
-        const float hi = a.clip_hi * mx;
-        float s = __fdiv_rn(hi - lo, 15.0f);
-        if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
-        const float inv = __fdiv_rn(1.0f, s);
-        const float nlo = -(lo * inv);
-
-        // ---- quantise, pack, store -----------------------------------------------------------------
-        int sum = 0;
-#pragma unroll
-        for (int hf = 0; hf < NH; ++hf)
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                uint32_t words[4], evs[4], ods[4];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    uint32_t ev = 0, od = 0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j], inv, nlo), 0.0f, 15.0f);
-                        const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
-                        ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
-                        od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
-                    }
-                    sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
-                    sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
-                    words[w] = ev | (od << 4);
-                    evs[w] = ev; ods[w] = od;
-                }
+        const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, ROT_OUT>(
+            raw, bop, wl, lbias, a.act_scale, ROT_OUT ? a.rot_out + m * (int64_t)K : nullptr, norm, a.clip_lo, a.clip_hi,
+            lane, pl.wbase, pl.rbase,
+            // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
+            [&]() { if (PREFETCH && mnext < a.M) load_token(mnext); },
+            [&](int hf, int b, const uint32_t (&words)[4], const uint32_t (&evs)[4], const uint32_t (&ods)[4]) {
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
                 if (a.Aq6) {
@@ -323,11 +91,10 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                         make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
                     *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
                 }
-            }
-        sum = wave_sum_i(sum);
+            });
         if (lane == 0) {
             basq_tokmeta mt;
-            mt.scale = s; mt.lo = lo; mt.rowsum = sum; mt.reserved = 0;
+            mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum; mt.reserved = 0;
             a.meta[m] = mt;
         }
     }

@@ -103,6 +103,19 @@ def test_decode_ragged(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=3 * M + N), rot_size=K if K != 96 else 32)
 
 
+@pytest.mark.parametrize("M,K,N,scaled,biased", [(1, 8192, 24, False, False), (4, 8192, 100, True, True), (3, 8192, 48, False, True), (16, 8192, 48, False, False),
+                                                 (3, 4096, 40, True, True), (4, 4096, 4096, False, True), (2, 4096, 17, True, False),
+                                                 (5, 4096, 4096, False, True)])
+def test_decode_one_launch(M, K, N, scaled, biased):
+    """Calls of at most 4 tokens with rot_size = K in {4096, 8192}, N <= 4096 and the streaming weight layout run
+    the whole layer in one kernel (basq_linear_fused); run_case checks its output against the two-call path bit
+    for bit, and that path against the oracle.  With and without s^a and the bias, ragged N; the cases above 4
+    tokens take the two-kernel path on the same shapes."""
+    lay = si.make_tiny(M, K, N, seed=M + K + N)
+    sa = np.random.default_rng(M + N).uniform(0.7, 1.5, K).astype(np.float32) if scaled else None
+    run_case(lay, act_scale=sa, use_bias=biased, use_out_bias=biased, use_blas_gemm=True)
+
+
 @pytest.mark.parametrize("M,N", [(16, 16392), (9, 16400), (8, 16392)])
 def test_decode_many_output_channels(M, N):
     """More than 1024 blocks of 16 output channels: with more than 8 tokens a workgroup takes two blocks
