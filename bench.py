@@ -36,7 +36,8 @@ MEASURED_TRAFFIC = {
     ("C2", "rotate_quant"): 27570516, ("C2", "gemm"): 170408395, ("C2", "gemm_fp6"): 240840227,
     ("C4", "rotate_quant"): 106123093, ("C4", "gemm"): 173675831, ("C4", "gemm_fp6"): 237421378,
     ("C5", "rotate_quant"): 109653302, ("C5", "gemm"): 945002621, ("C5", "gemm_fp6"): 1294344815,
-    ("C3_M16", "rotate_quant"): 302253, ("C3_M16", "gemm"): 8981508,
+    ("C3_M16", "rotate_quant"): 301233, ("C3_M16", "gemm"): 8985923,
+    ("C3_M1", "rotate_quant"): 44642, ("C3_M1", "gemm"): 8616106,
 }
 
 
