@@ -179,6 +179,17 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
 /* ---- offline helpers (not on the timed path) --------------------------------------------- */
 
 /*
+ * Offline weight rotation W' = W R (Sec. 4: the rotation of the activations is undone by folding R into the
+ * weights; Eq. 14 writes the layer as (W R)(R^-1 x)): every row of W is rotated blockwise by H_n/sqrt(n) exactly
+ * as basq_rotate_quant rotates a token (fp32), then rounded to bf16.
+ *   W          bf16 [N, ldw], ldw >= K, ldw % 8 == 0, 16-byte aligned;  rot_size as in basq_rotate_quant
+ *   W_rot      out, bf16 [N, K], 16-byte aligned
+ *   workspace  >= N*K*4 bytes (the fp32 rotation), 16-byte aligned, else BASQ_EWORKSPACE
+ */
+int basq_rotate_weights(const void* W, int32_t N, int32_t K, int64_t ldw, int32_t rot_size, void* W_rot,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Round-to-nearest per-output-channel asymmetric INT4 quantisation of rotated-basis weights
  * (weights are quantised per channel, Sec. 5 "Deployment Details"; asymmetric with a bf16
  * zero-point per the workload definition).  Per row n, every operation one fp32 operation:

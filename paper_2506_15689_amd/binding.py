@@ -21,7 +21,7 @@ BASQ_W_CANONICAL = 0
 BASQ_W_DECODE16 = 1
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
-           "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
            "basq_hadamard28", "basq_diag_stream", "basq_diag_read", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.basq_linear_fused.restype = c.c_int
     lib.basq_linear_fused.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32,
                                       vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, c.c_size_t, vp]
+    lib.basq_rotate_weights.restype = c.c_int
+    lib.basq_rotate_weights.argtypes = [vp, i32, i32, i64, i32, vp, vp, c.c_size_t, vp]
     lib.basq_quantize_weights.restype = c.c_int
     lib.basq_quantize_weights.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp]
     lib.basq_fused_bias.restype = c.c_int
@@ -178,6 +180,14 @@ def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
                                     _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
                                     _p(Wq6), _p(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def basq_rotate_weights(W: torch.Tensor, rot_size: int, W_rot: torch.Tensor, workspace: torch.Tensor, *,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+    """W bf16 [N, K] -> W_rot bf16 [N, K] = W . (H_n/sqrt(n)) blockwise; workspace >= N*K*4 bytes."""
+    N, K = W.shape
+    _check(load().basq_rotate_weights(_p(W), N, K, W.stride(0), rot_size, _p(W_rot), _p(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def basq_quantize_weights(W_rot: torch.Tensor, Wq: torch.Tensor, w_scale: torch.Tensor, w_zero: torch.Tensor,

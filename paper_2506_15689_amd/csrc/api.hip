@@ -262,6 +262,28 @@ int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_
     return launch_column_mean(a.rot_out, M, K, act_scale, bias_out, s);
 }
 
+int basq_rotate_weights(const void* W, int32_t N, int32_t K, int64_t ldw, int32_t rot_size, void* W_rot,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    RotateQuantArgs a{};
+    int rc = validate_rotate(W, N, K, ldw, rot_size, 4, 0, 1.0f, 1.0f, &a.pow2, &a.has28);
+    if (rc != BASQ_OK) return rc;
+    if (N < 1) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (!W_rot || !workspace) return fail(BASQ_EINVAL, "a pointer is null");
+    if (!aligned16(workspace) || !aligned16(W_rot)) return fail(BASQ_EINVAL, "W_rot and workspace must be 16-byte aligned");
+    const size_t need = (size_t)N * (size_t)K * sizeof(float);
+    if (workspace_bytes < need)
+        return fail(BASQ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    a.X = static_cast<const uint16_t*>(W);
+    a.M = N; a.K = K; a.ldx = ldw; a.rot_size = rot_size;
+    a.clip_lo = a.clip_hi = 1.0f;
+    a.group = K;
+    a.rot_out = static_cast<float*>(workspace);      // rotation-only mode: Aq/meta stay null
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = launch_rotate_quant(a, s);
+    if (rc != BASQ_OK) return rc;
+    return launch_f32_to_bf16(a.rot_out, static_cast<uint16_t*>(W_rot), (int64_t)N * K, s);
+}
+
 int basq_hadamard28(int8_t* out_host) {
     if (!out_host) return fail(BASQ_EINVAL, "out_host is null");
     const int8_t* h = hadamard28_host();

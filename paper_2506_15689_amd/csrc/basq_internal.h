@@ -80,6 +80,7 @@ int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw
                             uint16_t* w_scale, uint16_t* w_zero, float* w_sum, hipStream_t s);
 int launch_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const uint16_t* w_scale, const uint16_t* w_zero,
                       const float* bias, const float* layer_bias, float* out_bias, hipStream_t s);
+int launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s);
 int launch_column_mean(const float* r, int64_t M, int32_t K, const float* act_scale, float* out, hipStream_t s);
 
 // 28 x 28 Paley type-I matrix, row-major, built on the host at first use (hadamard28.hip).

@@ -1,6 +1,7 @@
 // Offline helpers: per-output-channel asymmetric INT4 weight quantisation (paper Sec. 5,
 // "Deployment Details": weights are quantised per channel), the fused bias W_hat b^c + b of
-// Eq. 14, and the column mean that calibrates the channel bias b^c (Sec. 3.2).  Not on the timed
+// Eq. 14, the column mean that calibrates the channel bias b^c (Sec. 3.2), and the fp32 -> bf16 pass that
+// finishes the offline weight rotation W' = W R (Sec. 4: the rotation is folded into the weights).  Not on the timed
 // path; written for clarity, one workgroup per row / one thread per column.
 #include "basq_internal.h"
 
@@ -114,6 +115,26 @@ int launch_column_mean(const float* r, int64_t M, int32_t K, const float* act_sc
     const unsigned blocks = (unsigned)((K + WQ_THREADS - 1) / WQ_THREADS);
     hipLaunchKernelGGL(column_mean_kernel, dim3(blocks), dim3(WQ_THREADS), 0, s, r, M, K, act_scale, out);
     return check_hip(hipGetLastError(), "column_mean launch");
+}
+
+namespace {
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ in, uint16_t* __restrict__ out, int64_t n4) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    const float4 v = reinterpret_cast<const float4*>(in)[i];
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+    o.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+    reinterpret_cast<uint2*>(out)[i] = o;
+}
+}  // namespace
+
+int launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s) {
+    const int64_t n4 = count / 4;                       // count is a multiple of 32 (K % 32 == 0)
+    const int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return fail(BASQ_EINVAL, "rotate_weights: matrix too large");
+    if (blocks > 0) hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, out, n4);
+    return check_hip(hipGetLastError(), "f32_to_bf16 launch");
 }
 
 }  // namespace basq

@@ -158,6 +158,10 @@ def test_zero_tokens_is_valid_without_a_launch(lib):
 
 
 def test_offline_helpers_reject_bad_arguments(lib):
+    assert lib.basq_rotate_weights(None, 8, 64, 64, 64, FAKE, FAKE, 1 << 20, None) == B.BASQ_EINVAL
+    assert lib.basq_rotate_weights(FAKE, 8, 64, 64, 48, FAKE, FAKE, 1 << 20, None) != 0       # 48 is no Hadamard size
+    assert lib.basq_rotate_weights(FAKE, 8, 64, 64, 64, FAKE, FAKE, 8 * 64 * 4 - 1, None) == B.BASQ_EWORKSPACE
+    assert lib.basq_rotate_weights(FAKE, 0, 64, 64, 64, FAKE, FAKE, 1 << 20, None) == B.BASQ_EINVAL
     assert lib.basq_quantize_weights(None, 8, 64, 64, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_quantize_weights(FAKE, 8, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_fused_bias(FAKE, 0, 64, FAKE, FAKE, None, None, FAKE, None) == B.BASQ_EINVAL

@@ -243,6 +243,31 @@ def test_weight_quantiser_and_fused_bias(N, K):
     np.testing.assert_allclose(ob.cpu().numpy(), oracle.fused_bias(wq, bc, lb), rtol=1e-6, atol=1e-6)
 
 
+@pytest.mark.parametrize("N,K,rot", [(40, 1024, 1024), (33, 1792, 1792), (24, 512, 128), (19, 8192, 8192)])
+def test_offline_weight_rotation(N, K, rot):
+    """W' = W R in bf16: the oracle's fp64 rotation rounded once to bf16.  The kernel rounds its fp32 rotation,
+    so a value that sits within an fp32 rounding error of a bf16 tie may land on the neighbouring bf16 number:
+    at most 1e-3 of the values, each by one unit in the last place.  And the reason the rotation may be folded
+    into the weights at all (Eq. 14): (X R)(W R)^T = X W^T, here to bf16 accuracy."""
+    dev = "cuda"
+    lay = si.make_tiny(32, K, N, seed=N + rot)
+    W = lay.W_rot                                                   # any bf16 matrix serves as the unrotated weights
+    w = oracle.bf16_to_f32(si.bf16_bits(W))
+    ref_bits = oracle.f64_to_bf16(oracle.rotate_f64(w, rot))
+    out = torch.full((N, K), float("nan"), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(N * K, dtype=torch.float32, device=dev)
+    B.basq_rotate_weights(W.to(dev), rot, out, ws)
+    torch.cuda.synchronize()
+    got_bits = si.bf16_bits(out.cpu())
+    diff = got_bits.astype(np.int32) - ref_bits.astype(np.int32)
+    assert (np.abs(diff) <= 1).all(), "a rotated weight is more than one bf16 step from the oracle's"
+    assert (diff != 0).mean() <= 1e-3, f"{(diff != 0).mean()} of the rotated weights differ"
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X)).astype(np.float64)
+    lhs = oracle.rotate_f64(x, rot) @ oracle.bf16_to_f32(got_bits).astype(np.float64).T
+    rhs = x @ w.astype(np.float64).T
+    assert np.abs(lhs - rhs).max() <= 2.0 ** -7 * np.abs(rhs).max()
+
+
 @pytest.mark.parametrize("K,rot", [(1024, 1024), (1792, 1792)])
 def test_bias_calibration(K, rot):
     dev = "cuda"
