@@ -59,7 +59,7 @@ def parse_args():
                    help="prefill GEMM on the f8f6f4 matrix-core path (codes repacked as exact fp6 values; default) "
                         "or on the int8 path; decode-sized M always streams the INT4 weights")
     p.add_argument("--weight-layout", default="stream", choices=["stream", "canonical"],
-                   help="decode shapes (M <= 16): weights in the weight-streaming layout (default) or canonical")
+                   help="decode shapes (M <= 128): weights in the weight-streaming layout (default) or canonical")
     p.add_argument("--rot-size", type=int, default=0, help="with --only rotate_quant: rotation block instead of the workload's")
     p.add_argument("--group-size", type=int, default=0,
                    help="with --only rotate_quant: channels per range (0 = per token); 128 with --rot-size 128 is the "
@@ -144,14 +144,14 @@ def main():
     B.basq_calibrate_bias(Xc, rot_size, None, bias, cal_ws)
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
-    use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > 16 and group in (0, K)
+    use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > B.STREAM_MAX_TOKENS and group in (0, K)
     Wq6 = None
     if use_fp6:                                # offline: the weights once more in the fp6 operand form
         Wq6 = B.alloc_fp6_buffer(N, K, dev)
         B.basq_pack_fp6(Wq, Wq6)
     # decode shapes stream the weights once per call: the streaming layout (offline repack), and as many
     # distinct copies as it takes to keep them out of the 256 MB last-level cache between calls
-    decode = M <= 16 and K % 128 == 0
+    decode = M <= B.STREAM_MAX_TOKENS and K % 128 == 0
     w_layout, wsets = B.BASQ_W_CANONICAL, [Wq]
     if decode:
         if args.weight_layout == "stream":
@@ -236,7 +236,7 @@ def main():
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
-    if args.M > 0 or args.no_bias or args.rot_size or args.group_size or (args.matrix_path == "int8" and M > 16):
+    if args.M > 0 or args.no_bias or args.rot_size or args.group_size or (args.matrix_path == "int8" and M > B.STREAM_MAX_TOKENS):
         MEASURED_TRAFFIC.clear()                  # the stored counters belong to the unmodified configurations
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -348,7 +348,7 @@ def main():
                    "weight_layout": "streaming (16-row blocks)" if w_layout == B.BASQ_W_DECODE16 else "canonical",
                    "step_launches": 1 if (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192)
                                           and rot_size == K) else 2,
-                   "matrix_path": "fp6" if use_fp6 else ("int8" if M > 16 else "int4 weight streaming")},
+                   "matrix_path": "fp6" if use_fp6 else ("int4 weight streaming" if decode else "int8")},
         "rotate_quant_GBps": rq_gbs,
         "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,

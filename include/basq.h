@@ -104,18 +104,18 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
  *
  *   Aq, meta   as written by basq_rotate_quant, [M, K/2] and [M]
  *   Wq         uint8 [N, K/2] with w_layout = BASQ_W_CANONICAL, or the weight-streaming layout of
- *              basq_pack_decode with w_layout = BASQ_W_DECODE16.  The latter is read by the M <= 16 path
- *              only: with M > 16 it needs the fp6 operands (which replace Wq), else BASQ_EUNSUPPORTED.
+ *              basq_pack_decode with w_layout = BASQ_W_DECODE16.  The latter is read by the M <= 128 path
+ *              only: with M > 128 it needs the fp6 operands (which replace Wq), else BASQ_EUNSUPPORTED.
  *   w_scale    bf16 [N] sw;  w_zero  bf16 [N] zp in code units (any real value)
  *   w_sum      fp32 [N] = sw_n * (sum_k q_w[n,k] - K * zp_n) = sum_k W_hat[n,k]
  *   out_bias   fp32 [N] c, or NULL (= 0)
  *   Y          out, bf16 [M, ldy], ldy >= N
  *   acc_out    out, optional debug dump of ACC, int32 [M, N]; NULL to skip
  *   Aq6, Wq6   optional, both or neither: the two code matrices in the fp6 operand form
- *              (basq_pack_fp6; Aq6 also straight from basq_rotate_quant).  With them, and M > 16, the
+ *              (basq_pack_fp6; Aq6 also straight from basq_rotate_quant).  With them, and M > 128, the
  *              product runs on the f8f6f4 matrix-core path at twice the int8 rate; ACC and Y are
  *              bit-identical to the int8 path.  Needs K % 128 == 0.
- * Any M >= 0, N >= 1; small M (decode) takes a weight-streaming path, same results.
+ * Any M >= 0, N >= 1; M <= 128 (decode, batched decode) takes a weight-streaming path, same results.
  */
 int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K,
                    const uint8_t* Wq, int32_t N, int32_t w_layout,
@@ -143,7 +143,7 @@ size_t basq_fp6_bytes(int64_t rows, int32_t K);
 int basq_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6, void* stream);
 
 /*
- * The weight-streaming layout for decode-sized calls (M <= 16; such a call is one pass over the weights and
+ * The weight-streaming layout for decode-sized calls (M <= 128; such a call is one pass over the weights and
  * bound by memory bandwidth, the decode case of Sec. 5.2's speed measurement).  The matrix-core operand of
  * that path puts 16 different rows on the 16 lanes of a quarter wavefront, so canonical weights are read in
  * 16-byte pieces of 16 rows at a time; here the kilobyte one wavefront load consumes is contiguous instead.
@@ -232,7 +232,7 @@ int basq_hadamard28(int8_t* out_host);
 int basq_diag_stream(const void* src, void* dst, void* meta, int64_t tokens, int32_t K, void* stream);
 
 /*
- * Read-only streaming kernel with the access pattern of the decode-sized product (M <= 16: one pass over the
+ * Read-only streaming kernel with the access pattern of the decode-sized product (M <= 128: one pass over the
  * weights, bound by memory bandwidth): `blocks` workgroups walk `bytes` (a multiple of 32768) of src in 32 KB
  * spans, every lane requesting eight 16-byte pieces before it consumes any; out receives blocks*256 uint32
  * checksums.

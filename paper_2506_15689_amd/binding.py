@@ -19,6 +19,7 @@ BASQ_EWORKSPACE = -3
 BASQ_EHIP = -4
 BASQ_W_CANONICAL = 0
 BASQ_W_DECODE16 = 1
+STREAM_MAX_TOKENS = 128      # calls of at most this many tokens take the weight-streaming kernel (K % 128 == 0)
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
            "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",

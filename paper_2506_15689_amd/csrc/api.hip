@@ -76,10 +76,10 @@ int validate_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_
 }
 
 int run_gemm(const GemmArgs& g, hipStream_t s) {
-    if (g.M <= 16 && g.K % 128 == 0) return launch_gemv_decode(g, s);
+    if (g.M <= GEMV_MAX_TOKENS && g.K % 128 == 0) return launch_gemv_decode(g, s);
     if (gemm_fp6_applicable(g)) return launch_gemm_fp6(g, s);
     if (g.w_layout != BASQ_W_CANONICAL)
-        return fail(BASQ_EUNSUPPORTED, "more than 16 tokens with the streaming weight layout need the fp6 operands "
+        return fail(BASQ_EUNSUPPORTED, "more than 128 tokens with the streaming weight layout need the fp6 operands "
                                         "(the int8 kernels read canonical weights)");
     return launch_gemm_prefill(g, s);
 }
@@ -205,15 +205,15 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
     // the fp6 copy of the codes is only worth making when the matrix-core path will take it
     uint8_t* Aq6 = nullptr;
-    if (Wq6 && M > 16)
+    if (Wq6 && M > GEMV_MAX_TOKENS)
         Aq6 = reinterpret_cast<uint8_t*>(meta) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
     a.group = K;
     a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
                w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, w_layout};
-    if (w_layout != BASQ_W_CANONICAL && M > 16 && !gemm_fp6_applicable(g))      // before anything is launched
-        return fail(BASQ_EUNSUPPORTED, "more than 16 tokens with the streaming weight layout need the fp6 operands "
+    if (w_layout != BASQ_W_CANONICAL && M > GEMV_MAX_TOKENS && !gemm_fp6_applicable(g))      // before anything is launched
+        return fail(BASQ_EUNSUPPORTED, "more than 128 tokens with the streaming weight layout need the fp6 operands "
                                         "(the int8 kernels read canonical weights)");
     if (linear_decode_applicable(a, g)) return launch_linear_decode(a, g, s);      // a few tokens: one launch
     rc = launch_rotate_quant(a, s);

@@ -59,13 +59,14 @@ struct GemmArgs {
     // fp6 operand form of both matrices; both or neither (gemm_w4a4_fp6.hip)
     const uint8_t* Aq6;
     const uint8_t* Wq6;
-    int32_t w_layout;         // layout of Wq: BASQ_W_CANONICAL, or BASQ_W_DECODE16 (read by the M <= 16 kernel only)
+    int32_t w_layout;         // layout of Wq: BASQ_W_CANONICAL, or BASQ_W_DECODE16 (read by the weight-streaming kernel only)
 };
 int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 // direct-to-LDS kernel for K % 256 == 0 (gemm_w4a4_direct.hip)
 bool gemm_direct_applicable(const GemmArgs& a);
 int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
-int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= 16
+constexpr int GEMV_MAX_TOKENS = 128;                          // above it the tiled GEMMs take over
+int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= GEMV_MAX_TOKENS, K % 128 == 0
 // one launch for the whole layer at decode size (linear_decode.hip)
 bool linear_decode_applicable(const RotateQuantArgs& q, const GemmArgs& g);
 int launch_linear_decode(const RotateQuantArgs& q, const GemmArgs& g, hipStream_t s);

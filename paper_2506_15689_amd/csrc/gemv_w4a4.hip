@@ -1,10 +1,12 @@
-// Decode-shaped W4A4 product (M <= 16 tokens): one pass over the packed weights, bound by HBM
-// bandwidth.  Same arithmetic as the prefill GEMM (ACC in INT32, fused de-quantisation).
+// Weight-streaming W4A4 product for few tokens (M <= 128: decode, batched decode, speculative decoding): one
+// pass over the packed 4-bit weights, bound by HBM bandwidth up to about 64 tokens.  Same arithmetic as the
+// prefill GEMM (ACC in INT32, fused de-quantisation).
 //
-// A workgroup owns 16 output channels; its waves split K.  Each lane issues all of its 16-byte
-// weight loads before it consumes any, so the whole weight matrix is in flight at once.  The
-// 16 x 16 x 64 int8 MFMA takes the 16 weight rows as one operand and the (zero padded) tokens as
-// the other; nibbles are split into low/high words exactly as in the prefill kernel.
+// A workgroup owns 16 or 32 output channels; its waves split K.  Each lane issues a batch of 16-byte weight
+// loads before it consumes any, so the whole weight matrix is in flight at once.  The 16 x 16 x 64 int8 MFMA
+// takes 16 weight rows as one operand and 16 (zero padded) tokens as the other; more tokens are more token
+// tiles against the same weight registers.  Nibbles are split into low/high words exactly as in the prefill
+// kernel.
 //
 // Weight layouts.  The MFMA operand puts 16 different rows on the 16 lanes of a quarter wave, so on
 // canonical [N, K/2] weights every load instruction touches 16 rows x 64 bytes and each 128-byte line
@@ -18,28 +20,30 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-#ifndef GV_WAVES_CFG
-#define GV_WAVES_CFG 4
-#endif
-constexpr int GV_WAVES = GV_WAVES_CFG;
-constexpr int GV_THREADS = GV_WAVES * 64;
-static_assert(GV_THREADS >= 256, "the epilogue maps one thread to each of the 16 x 16 outputs");
-constexpr int GV_ROWS = 16;        // output channels per workgroup
+constexpr int GV_WAVES = 4;
+constexpr int GV_THREADS = GV_WAVES * 64;           // the epilogue maps one thread to each of a tile's 16 x 16 outputs
+constexpr int GV_ROWS = 16;                         // output channels per tile
 
-// GV_MAX_STEPS: 64-byte k-chunks per lane held in registers at once (all of their loads are in flight together).
-// TILES: 16-row tiles per workgroup; the tiles share the activation operand, so with 16 tokens (where the
-// activations a workgroup reads from L2 are as many bytes as the weights of one tile) two tiles halve that traffic.
-template <bool STREAM_LAYOUT, int GV_MAX_STEPS, int TILES>
+// STEPS: 64-byte k-chunks per lane held in registers at once (all of their loads are in flight together).
+// TILES: 16-row weight tiles per workgroup; they share the activation operand, which at 16 tokens is as many
+//        L2 bytes per workgroup as one tile's weights.
+// TT:    16-token tiles (M <= 16 * TT); they share the weight registers.
+template <bool STREAM_LAYOUT, int STEPS, int TILES, int TT>
 __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
-    __shared__ int part[GV_WAVES][TILES * GV_ROWS * 16];
+    constexpr int NT = TILES * TT;                  // accumulator tiles per wave
+    constexpr bool TWO_CHAINS = NT <= 2;            // few tiles: low and high nibbles on separate MFMA chains
+    __shared__ int part[NT * 256];                  // cross-wave sums (integer adds: any order gives the same bits)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n0 = blockIdx.x * (GV_ROWS * TILES);
     const int KB = a.K / 2;
     const int nchunks = KB / 64;               // 64-byte chunks per row (K % 128 == 0 checked by the caller)
     const int row = lane & 15, sub = lane >> 4;
+    const int M = (int)a.M;
 
-    const bool t_ok = row < a.M;               // the same lane index selects the token on the other operand
+#pragma unroll
+    for (int i = 0; i < NT; ++i) part[i * 256 + tid] = 0;
+
     // chunk c of this lane: canonical = 16 bytes of row n at 64c + 16sub; streaming = piece `lane` of the
     // 16-row block's c-th KB (rows past N are stored as zeros there; a whole block past N does not exist)
     const uint8_t* wrow[TILES];
@@ -52,21 +56,24 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
                                 : a.Wq + (int64_t)(w_ok[t] ? n : 0) * KB + sub * 16;
     }
     constexpr int WSTEP = STREAM_LAYOUT ? 1024 : 64;
-    const uint8_t* arow = a.Aq + (int64_t)(t_ok ? row : 0) * KB + sub * 16;
+    // the same lane index selects the token of tile tt on the other operand
+    const uint8_t* arow[TT];
+    bool t_ok[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        t_ok[tt] = 16 * tt + row < M;
+        arow[tt] = a.Aq + (int64_t)(t_ok[tt] ? 16 * tt + row : 0) * KB + sub * 16;
+    }
 
     // epilogue constants of the outputs this thread will finish (16 consecutive channels of one token per
     // 16 threads, one such output per tile): requested now so that their latency overlaps the weight stream
     const int orow = tid & 15, otok = tid >> 4;
-    basq_tokmeta mt = {0.f, 0.f, 0, 0};
-    if (otok < a.M && otok < 16) mt = a.meta[otok];
     float sw[TILES], zp[TILES], ws[TILES], cb[TILES];
-    bool out_ok[TILES];
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
         const int on = n0 + GV_ROWS * t + orow;
-        out_ok[t] = otok < a.M && on < a.N && otok < 16;
         sw[t] = zp[t] = ws[t] = cb[t] = 0.f;
-        if (out_ok[t]) {
+        if (on < a.N) {
             sw[t] = bf16_to_f32(a.w_scale[on]);
             zp[t] = bf16_to_f32(a.w_zero[on]);
             ws[t] = a.w_sum[on];
@@ -74,13 +81,15 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
         }
     }
 
-    v4i acc[TILES], acc2[TILES];               // two chains per tile: low and high nibbles
+    v4i acc[NT], acc2[TWO_CHAINS ? NT : 1];
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) acc[t] = acc2[t] = v4i{0, 0, 0, 0};
-    for (int c0 = wave; c0 < nchunks; c0 += GV_WAVES * GV_MAX_STEPS) {
-        v4i w[TILES][GV_MAX_STEPS], x[GV_MAX_STEPS];
+    for (int i = 0; i < NT; ++i) acc[i] = v4i{0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < GV_MAX_STEPS; ++i) {
+    for (int i = 0; i < (TWO_CHAINS ? NT : 1); ++i) acc2[i] = v4i{0, 0, 0, 0};
+    for (int c0 = wave; c0 < nchunks; c0 += GV_WAVES * STEPS) {
+        v4i w[TILES][STEPS], x[TT][STEPS];
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
             const int c = c0 + i * GV_WAVES;
             const bool ok = c < nchunks;
             // the weights are read once per call: streaming (non-temporal) loads
@@ -88,40 +97,52 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
             for (int t = 0; t < TILES; ++t)
                 w[t][i] = (ok && w_ok[t]) ? __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wrow[t] + c * WSTEP))
                                           : v4i{0, 0, 0, 0};
-            x[i] = (ok && t_ok) ? *reinterpret_cast<const v4i*>(arow + c * 64) : v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                x[tt][i] = (ok && t_ok[tt]) ? *reinterpret_cast<const v4i*>(arow[tt] + c * 64) : v4i{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int i = 0; i < GV_MAX_STEPS; ++i) {
-            const v4i xlo = x[i] & 0x0F0F0F0F, xhi = (x[i] >> 4) & 0x0F0F0F0F;
+        for (int i = 0; i < STEPS; ++i) {
+            v4i wlo[TILES], whi[TILES];
 #pragma unroll
-            for (int t = 0; t < TILES; ++t) {
-                const v4i wlo = w[t][i] & 0x0F0F0F0F, whi = (w[t][i] >> 4) & 0x0F0F0F0F;
-                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wlo, xlo, acc[t], 0, 0, 0);
-                acc2[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi, xhi, acc2[t], 0, 0, 0);
+            for (int t = 0; t < TILES; ++t) { wlo[t] = w[t][i] & 0x0F0F0F0F; whi[t] = (w[t][i] >> 4) & 0x0F0F0F0F; }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const v4i xlo = x[tt][i] & 0x0F0F0F0F, xhi = (x[tt][i] >> 4) & 0x0F0F0F0F;
+#pragma unroll
+                for (int t = 0; t < TILES; ++t) {
+                    const int at = t * TT + tt;
+                    acc[at] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wlo[t], xlo, acc[at], 0, 0, 0);
+                    if (TWO_CHAINS) acc2[at] = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi[t], xhi, acc2[at], 0, 0, 0);
+                    else acc[at] = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi[t], xhi, acc[at], 0, 0, 0);
+                }
             }
         }
     }
     // accumulator register r of lane l: weight row 4*(l/16) + r, token l%16
+    __syncthreads();                                // every wave has zeroed its share of `part`
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        acc[t] += acc2[t];
+    for (int at = 0; at < NT; ++at) {
+        if (TWO_CHAINS) acc[at] += acc2[at];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) part[wave][t * 256 + (4 * sub + r) * 16 + row] = acc[t][r];
+        for (int r = 0; r < 4; ++r) atomicAdd(&part[at * 256 + (4 * sub + r) * 16 + row], acc[at][r]);
     }
     __syncthreads();
 
-    if (GV_THREADS > 256 && tid >= 256) return;
 #pragma unroll
-    for (int t = 0; t < TILES; ++t) {
-        int av = 0;
+    for (int tt = 0; tt < TT; ++tt) {
+        const int tok = 16 * tt + otok;
+        if (tok >= M) continue;
+        const basq_tokmeta mt = a.meta[tok];
 #pragma unroll
-        for (int w = 0; w < GV_WAVES; ++w) av += part[w][t * 256 + orow * 16 + otok];
-        if (out_ok[t]) {
+        for (int t = 0; t < TILES; ++t) {
             const int on = n0 + GV_ROWS * t + orow;
-            const float tt = (float)av - zp[t] * (float)mt.rowsum;
-            const float y = fmaf(mt.scale * sw[t], tt, fmaf(mt.lo, ws[t], cb[t]));
-            a.Y[(int64_t)otok * a.ldy + on] = f32_to_bf16(y);
-            if (a.acc_out) a.acc_out[(int64_t)otok * a.N + on] = av;
+            if (on >= a.N) continue;
+            const int av = part[(t * TT + tt) * 256 + orow * 16 + otok];
+            const float tv = (float)av - zp[t] * (float)mt.rowsum;
+            const float y = fmaf(mt.scale * sw[t], tv, fmaf(mt.lo, ws[t], cb[t]));
+            a.Y[(int64_t)tok * a.ldy + on] = f32_to_bf16(y);
+            if (a.acc_out) a.acc_out[(int64_t)tok * a.N + on] = av;
         }
     }
 }
@@ -152,23 +173,43 @@ int launch_pack_decode16(const uint8_t* Wq, int32_t N, int32_t K, uint8_t* out, 
     return check_hip(hipGetLastError(), "pack_decode launch");
 }
 
+template <bool SL, int STEPS, int TILES, int TT>
+static void launch_gemv_cfg(const GemmArgs& a, hipStream_t s, int blocks16) {
+    hipLaunchKernelGGL((gemv_w4a4_kernel<SL, STEPS, TILES, TT>), dim3((unsigned)((blocks16 + TILES - 1) / TILES)),
+                       dim3(GV_THREADS), 0, s, a);
+}
+
+template <bool SL, int STEPS, int TT>
+static void launch_gemv_tiles(const GemmArgs& a, hipStream_t s, int blocks16) {
+    // More weight tiles per workgroup = fewer passes over the activations, which is what bounds the kernel from
+    // 32 tokens on -- as long as the workgroups still fill the chip (measured on N = 4096, 12288, 28672)
+    if (blocks16 >= 1536) launch_gemv_cfg<SL, STEPS, 4, TT>(a, s, blocks16);
+    else if (blocks16 >= 256) launch_gemv_cfg<SL, STEPS, 2, TT>(a, s, blocks16);
+    else launch_gemv_cfg<SL, STEPS, 1, TT>(a, s, blocks16);
+}
+
 template <bool SL>
 static void launch_gemv_layout(const GemmArgs& a, hipStream_t s) {
     const int blocks16 = (a.N + GV_ROWS - 1) / GV_ROWS;
-    // long rows: twice the loads in flight per lane (measured: K = 8192 gains 6 %, K = 4096 loses 5 %)
-    const bool deep = a.K / 128 > 32 * GV_WAVES / 4;
-    // two tiles per workgroup once the activations weigh in (more than 8 tokens) and the chip stays filled
-    const bool two = a.M > 8 && blocks16 >= 4 * 256;
-    if (two)
-        hipLaunchKernelGGL((gemv_w4a4_kernel<SL, 8, 2>), dim3((unsigned)((blocks16 + 1) / 2)), dim3(GV_THREADS), 0, s, a);
-    else if (deep)
-        hipLaunchKernelGGL((gemv_w4a4_kernel<SL, 16, 1>), dim3((unsigned)blocks16), dim3(GV_THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL((gemv_w4a4_kernel<SL, 8, 1>), dim3((unsigned)blocks16), dim3(GV_THREADS), 0, s, a);
+    if (a.M <= 16) {
+        // long rows: twice the loads in flight per lane (measured: K = 8192 gains 6 %, K = 4096 loses 5 %)
+        const bool deep = a.K / 128 > 32;
+        // two tiles per workgroup once the activations weigh in (more than 8 tokens) and the chip stays filled
+        if (a.M > 8 && blocks16 >= 4 * 256) launch_gemv_cfg<SL, 8, 2, 1>(a, s, blocks16);
+        else if (deep) launch_gemv_cfg<SL, 16, 1, 1>(a, s, blocks16);
+        else launch_gemv_cfg<SL, 8, 1, 1>(a, s, blocks16);
+    } else if (a.M <= 32) {
+        launch_gemv_tiles<SL, 2, 2>(a, s, blocks16);
+    } else if (a.M <= 64) {
+        launch_gemv_tiles<SL, 2, 4>(a, s, blocks16);
+    } else {
+        launch_gemv_tiles<SL, 1, 8>(a, s, blocks16);
+    }
 }
 
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s) {
     if (a.M == 0) return BASQ_OK;
+    if (a.M > GEMV_MAX_TOKENS) return fail(BASQ_EINVAL, "weight-streaming kernel: more than %d tokens", GEMV_MAX_TOKENS);
     if (a.w_layout == BASQ_W_DECODE16) launch_gemv_layout<true>(a, s);
     else launch_gemv_layout<false>(a, s);
     return check_hip(hipGetLastError(), "w4a4_gemv launch");

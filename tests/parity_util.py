@@ -141,19 +141,19 @@ def run_gpu(case: Case, d: DeviceCase) -> GpuResult:
         assert torch.equal(Aq2, Aq) and torch.equal(meta2, meta), "rotate_quant with and without the fp6 output"
         res.a6, res.w6 = A6.cpu().numpy(), W6.cpu().numpy()
         res.acc6, res.y6_bits, res.y6_fused_bits = acc6.cpu().numpy(), si.bf16_bits(Y6.cpu()), si.bf16_bits(Y6f.cpu())
-        # third pass: weights in the streaming layout (read by the M <= 16 kernel; larger M runs on the fp6
+        # third pass: weights in the streaming layout (read by the weight-streaming kernel; larger M runs on the fp6
         # operands and must not touch Wq at all)
         Wd = torch.empty(B.basq_decode_bytes(N, K), dtype=torch.uint8, device=dev).fill_(0xEE)
         B.basq_pack_decode(d.Wq, Wd)
         Yd = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
         Ydf = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=dev)
         accd = torch.full((M, N), -1, dtype=torch.int32, device=dev)
-        fp6 = dict(Aq6=A6, Wq6=W6) if M > 16 else {}
+        fp6 = dict(Aq6=A6, Wq6=W6) if M > B.STREAM_MAX_TOKENS else {}
         B.basq_w4a4_gemm(Aq, meta, Wd, d.w_scale, d.w_zero, d.w_sum, d.out_bias, Yd, accd,
                          w_layout=B.BASQ_W_DECODE16, N=N, **fp6)
         B.basq_linear_fused(d.X, case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, Wd, d.w_scale,
                             d.w_zero, d.w_sum, d.out_bias, Ydf, ws, w_layout=B.BASQ_W_DECODE16, N=N,
-                            Wq6=W6 if M > 16 else None)
+                            Wq6=W6 if M > B.STREAM_MAX_TOKENS else None)
         torch.cuda.synchronize()
         res.wd, res.accd = Wd.cpu().numpy(), accd.cpu().numpy()
         res.yd_bits, res.yd_fused_bits = si.bf16_bits(Yd.cpu()), si.bf16_bits(Ydf.cpu())

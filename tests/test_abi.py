@@ -140,15 +140,15 @@ def test_decode_layout_sizes_and_argument_checks(lib):
     assert lib.basq_pack_decode(None, 8, 128, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_pack_decode(FAKE, 0, 128, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_pack_decode(FAKE, 8, 128, ctypes.c_void_p(0x1008), None) == B.BASQ_EINVAL
-    # the streaming layout: K % 128, and more than 16 tokens only with the fp6 operands
+    # the streaming layout: K % 128, and more than 128 tokens only with the fp6 operands
     gemm = lambda M, K, layout, a6=None, w6=None: lib.basq_w4a4_gemm(
         FAKE, FAKE, M, K, FAKE, 32, layout, FAKE, FAKE, FAKE, None, FAKE, 32, None, a6, w6, None)
     assert gemm(4, 96, B.BASQ_W_DECODE16) == B.BASQ_EINVAL
-    assert gemm(17, 256, B.BASQ_W_DECODE16) == B.BASQ_EUNSUPPORTED
+    assert gemm(129, 256, B.BASQ_W_DECODE16) == B.BASQ_EUNSUPPORTED
     assert "fp6" in B.basq_last_error()
     assert gemm(4, 256, 2) == B.BASQ_EUNSUPPORTED
     ws = ctypes.c_void_p(0x100000)
-    assert lib.basq_linear_fused(FAKE, 17, 256, 256, 256, None, None, 0.9, 0.9, 4, 0, FAKE, 32, B.BASQ_W_DECODE16,
+    assert lib.basq_linear_fused(FAKE, 129, 256, 256, 256, None, None, 0.9, 0.9, 4, 0, FAKE, 32, B.BASQ_W_DECODE16,
                                  FAKE, FAKE, FAKE, None, FAKE, 32, None, ws, 1 << 30, None) == B.BASQ_EUNSUPPORTED
 
 

@@ -77,7 +77,7 @@ def run_fullsize(name, n_rows, n_cols, M=None):
     assert torch.equal(Y, Yf), "fused call differs from the two-call path"
 
     # ---- the fp6 matrix-core path (what bench.py times for prefill shapes): same bits everywhere
-    if M > 16:
+    if M > B.STREAM_MAX_TOKENS:
         Wq6 = B.alloc_fp6_buffer(N, K, dev)
         B.basq_pack_fp6(Wq, Wq6)
         Aq6 = B.alloc_fp6_buffer(M, K, dev)
@@ -104,12 +104,12 @@ def run_fullsize(name, n_rows, n_cols, M=None):
                 np.testing.assert_array_equal(got[:, rb].cpu().numpy(), ref6, err_msg=f"fp6 form of the {name6}, block {rb}")
         del Wq6, Aq6, Aq2, meta2, acc6, Y6, Y6f
 
-    # ---- a decode-sized call (the first 16 tokens) on the whole weight matrix in the streaming layout: the
-    # bits of the canonical-layout call, which in turn equal the rows of the full product checked below
-    if K % 128 == 0:
+    # ---- decode-sized calls (the first 16 and the first 100 tokens) on the whole weight matrix in the streaming
+    # layout: the bits of the canonical-layout call, which in turn equal the rows of the full product checked below
+    for m16 in ((16, 100) if K % 128 == 0 else ()):
         Wd = torch.empty(B.basq_decode_bytes(N, K), dtype=torch.uint8, device=dev)
         B.basq_pack_decode(Wq, Wd)
-        m16 = min(M, 16)
+        m16 = min(M, m16)
         accc = torch.empty((m16, N), dtype=torch.int32, device=dev)
         accd = torch.empty((m16, N), dtype=torch.int32, device=dev)
         Yc = torch.empty((m16, N), dtype=torch.bfloat16, device=dev)

@@ -41,15 +41,15 @@ def test_c1_full():
     run_case(si.make_layer(si.CONFIGS["C1"]))
 
 
-@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (33, 256, 40), (17, 4096, 96)])
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (161, 256, 40), (129, 4096, 96)])
 def test_ragged_multi_tile(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=M))
 
 
-@pytest.mark.parametrize("M,K,N", [(17, 128, 8), (40, 384, 264), (290, 640, 130)])
+@pytest.mark.parametrize("M,K,N", [(129, 128, 8), (140, 384, 264), (290, 640, 130)])
 def test_short_k_on_the_fp6_path(M, K, N):
     """One, three and five K-steps of the fp6 GEMM's stage ring (its prologue fills two stages), M just above
-    the decode threshold, N below one MFMA tile."""
+    the weight-streaming threshold, N below one MFMA tile."""
     run_case(si.make_tiny(M, K, N, seed=K + M), rot_size=128)
 
 
@@ -114,6 +114,15 @@ def test_decode_one_launch(M, K, N, scaled, biased):
     lay = si.make_tiny(M, K, N, seed=M + K + N)
     sa = np.random.default_rng(M + N).uniform(0.7, 1.5, K).astype(np.float32) if scaled else None
     run_case(lay, act_scale=sa, use_bias=biased, use_out_bias=biased, use_blas_gemm=True)
+
+
+@pytest.mark.parametrize("M,K,N", [(17, 4096, 96), (32, 512, 40), (33, 256, 100), (64, 1024, 1024), (65, 128, 24), (100, 640, 328),
+                                   (128, 2048, 136), (40, 128, 16392), (128, 256, 16400), (50, 8192, 64)])
+def test_batched_decode(M, K, N):
+    """17 to 128 tokens stay on the weight-streaming kernel: two, four or eight token tiles against the same
+    weight registers; one or (from 1024 blocks of 16 output channels) two weight tiles per workgroup; ragged
+    token tiles, ragged and odd block counts, K from one chunk per row to 64."""
+    run_case(si.make_tiny(M, K, N, seed=M * 7 + N), rot_size=K if (K & (K - 1)) == 0 else 128, use_blas_gemm=True)
 
 
 @pytest.mark.parametrize("M,N", [(16, 16392), (9, 16400), (8, 16392)])
