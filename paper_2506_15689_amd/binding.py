@@ -10,7 +10,7 @@ from typing import Optional, Tuple
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("BASQ_LIB", os.path.join(_PKG, "libbasq.so"))   # BASQ_LIB: a tuning build of the same library
+LIB_PATH = os.path.join(_PKG, "libbasq.so")
 
 BASQ_OK = 0
 BASQ_EINVAL = -1
