@@ -109,7 +109,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the layer shards over tokens or output channels without communication, see DESIGN.md)",
+              "(the layer shards over tokens or output channels without communication)",
               file=sys.stderr)
         sys.exit(2)
 
