@@ -497,6 +497,57 @@ def linear(x: np.ndarray, rot_size: int, bias: Optional[np.ndarray], act_scale: 
     return LinearResult(r, tq, acc, y, f64_to_bf16(y))
 
 
+def group_colsums(wq: WeightQuant, group_size: int) -> np.ndarray:
+    """colsum[g, n] = sum of the weight codes of output channel n over the K-channels of group g; int32 [K/G, N]."""
+    N, K = wq.codes.shape
+    G = int(group_size)
+    assert K % G == 0
+    return wq.codes.astype(np.int64).reshape(N, K // G, G).sum(axis=2).T.astype(np.int32).copy()
+
+
+def dequant_grouped(acc_g: np.ndarray, tq: TokenQuant, wq: WeightQuant, c: Optional[np.ndarray]) -> np.ndarray:
+    """Group-wise activation ranges (every run of G channels of a token has its own s, z; Eq. 4 per group):
+
+        Y[m, n] = sw_n * ( sum_g ( s_mg ACC_g[m, n] + z_mg colsum_g[n] ) - zp_n * sum_g ( s_mg rowsum_mg + G z_mg ) ) + c_n
+
+    acc_g: int [K/G, M, N], the integer products of one group each.  It is the per-token formula of dequant()
+    applied to each group with its own activation constants and the group's share of the weight sums."""
+    ng, M, N = acc_g.shape
+    K = wq.codes.shape[1]
+    G = K // ng
+    assert tq.scale.shape == (M, ng)
+    s = tq.scale.astype(np.float64)
+    z = tq.lo.astype(np.float64)
+    rs = tq.rowsum.astype(np.float64)
+    cs = group_colsums(wq, G).astype(np.float64)                     # [ng, N]
+    f = np.zeros((M, N), dtype=np.float64)
+    for g in range(ng):
+        f += s[:, g:g + 1] * acc_g[g].astype(np.float64) + z[:, g:g + 1] * cs[g][None, :]
+    rterm = (s * rs + G * z).sum(axis=1)[:, None]
+    sw = wq.scale.astype(np.float64)[None, :]
+    zp = wq.zero.astype(np.float64)[None, :]
+    y = sw * (f - zp * rterm)
+    if c is not None:
+        y = y + np.asarray(c, dtype=np.float64)[None, :]
+    return y
+
+
+def linear_grouped(x: np.ndarray, rot_size: int, bias: Optional[np.ndarray], act_scale: Optional[np.ndarray],
+                   clip_lo: float, clip_hi: float, group_size: int, wq: WeightQuant, c: Optional[np.ndarray],
+                   *, r: Optional[np.ndarray] = None) -> LinearResult:
+    """The layer with group-wise activation ranges, by its definition: the de-quantised activations
+    x_hat = s_mg q + z_mg (Eq. 4 per group) times the de-quantised weights W_hat = sw (q_w - zp), plus c, in fp64.
+    ``acc`` of the result is the plain integer product of the codes (all groups together)."""
+    if r is None:
+        r = rotate(x, rot_size)
+    tq = quantize_tokens(r, bias, act_scale, clip_lo, clip_hi, group_size=group_size)
+    y = dequantize_tokens(tq) @ dequantize_weights(wq).T
+    if c is not None:
+        y = y + np.asarray(c, dtype=np.float64)[None, :]
+    acc = int_gemm_blas(tq.codes, wq.codes)
+    return LinearResult(r, tq, acc, y, f64_to_bf16(y))
+
+
 def linear_full_precision(x: np.ndarray, rot_size: int, w_rot: np.ndarray,
                           layer_bias: Optional[np.ndarray] = None) -> np.ndarray:
     """Unquantised layer (X R) W'^T + b in fp64 -- not a parity target; used for the Eq. 14

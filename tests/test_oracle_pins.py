@@ -539,3 +539,49 @@ def test_decode_layout_is_the_stated_permutation():
     b = oracle.pack_decode16(one)
     where = 1 * 16 * 192 + 2 * 1024 + (16 * 1 + 5) * 16 + 6
     assert np.flatnonzero(b).tolist() == [where] and b[where] == 0xA7
+
+
+def test_groupwise_layer_against_its_definition_and_the_per_token_case():
+    """oracle.linear_grouped is the product of the de-quantised operands; oracle.dequant_grouped is the
+    integer-structured formula a kernel evaluates (per-group integer products, group scales, column sums per
+    group).  Two derivations of the same number: they must agree to fp64 rounding, a brute-force loop over
+    (m, n, k) must agree with both, and with one group per token both must give oracle.linear's bits."""
+    rng = np.random.default_rng(23)
+    M, K, N, G = 6, 256, 10, 64
+    x = (rng.standard_normal((M, K)) * (1 + 4 * (rng.random(K) < 0.05))).astype(np.float32)
+    x = oracle.bf16_to_f32(oracle.f64_to_bf16(x))
+    w = oracle.bf16_to_f32(oracle.f64_to_bf16(rng.standard_normal((N, K)) * 0.02))
+    wq = oracle.quantize_weights(w)
+    bias = rng.standard_normal(K).astype(np.float32) * 0.1
+    c = rng.standard_normal(N).astype(np.float32)
+    res = oracle.linear_grouped(x, 64, bias, None, 0.9, 0.95, G, wq, c)
+    assert res.tq.scale.shape == (M, K // G)
+    # integer-structured formula on per-group integer products
+    qa = res.tq.codes.astype(np.int64).reshape(M, K // G, G)
+    qw = wq.codes.astype(np.int64).reshape(N, K // G, G)
+    acc_g = np.einsum("mgk,ngk->gmn", qa, qw)
+    y2 = oracle.dequant_grouped(acc_g, res.tq, wq, c)
+    np.testing.assert_allclose(y2, res.y, rtol=1e-12, atol=1e-12 * np.abs(res.y).max())
+    np.testing.assert_array_equal(acc_g.sum(axis=0), res.acc)
+    # brute force from Eq. 4 element by element
+    sw, zp = wq.scale.astype(np.float64), wq.zero.astype(np.float64)
+    for m in (0, M - 1):
+        for n in (0, N - 1):
+            tot = 0.0
+            for k in range(K):
+                g = k // G
+                xh = float(res.tq.codes[m, k]) * float(res.tq.scale[m, g]) + float(res.tq.lo[m, g])
+                tot += xh * sw[n] * (float(wq.codes[n, k]) - zp[n])
+            assert abs(tot + float(c[n]) - res.y[m, n]) <= 1e-10 * np.abs(res.y).max()
+    # the group column sums are the shares of the per-channel column sum
+    np.testing.assert_array_equal(oracle.group_colsums(wq, G).sum(axis=0), wq.colsum)
+    # one group per token: the per-token layer
+    one = oracle.linear_grouped(x, 64, bias, None, 0.9, 0.95, K, wq, c)
+    ref = oracle.linear(x, 64, bias, None, 0.9, 0.95, wq, c)
+    np.testing.assert_array_equal(one.tq.codes, ref.tq.codes)
+    np.testing.assert_array_equal(one.y_bf16, ref.y_bf16)
+    # and finer ranges can only lower the quantisation error of the activations
+    xr = oracle.rotate(x, 64).astype(np.float64) - bias
+    e_tok = np.abs(oracle.dequantize_tokens(ref.tq) - xr).mean()
+    e_grp = np.abs(oracle.dequantize_tokens(res.tq) - xr).mean()
+    assert e_grp < e_tok
