@@ -82,7 +82,8 @@ const char* basq_last_error(void);
  *              multiple of 32 that divides K: every run of group_size consecutive channels gets its own
  *              range, steps 4-6 above and the record apply per group (per-head quantisation of q, k and
  *              the KV cache with rot_size = group_size = head_dim; Sec. 5 "Deployment Details").  Such
- *              codes are not an input of basq_w4a4_gemm.
+ *              codes are not an input of basq_w4a4_gemm; with group_size = 128 they are the input of
+ *              basq_w4a4_gemm_grouped.
  *   Aq         out, uint8 [M, K/2] canonical packed codes
  *   meta       out, [M, K/group_size] records, token-major (group_size 0 counts as K)
  *   rot_out    out, optional debug dump of r, fp32 [M, K]; NULL to skip
@@ -122,6 +123,30 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
                    const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
                    void* Y, int64_t ldy, int32_t* acc_out,
                    const uint8_t* Aq6, const uint8_t* Wq6, void* stream);
+
+/*
+ * The same product for activations quantised in groups of 128 channels (basq_rotate_quant with group_size = 128:
+ * every group g of token m has its own step s_mg, lower bound z_mg and code sum rowsum_mg; Eq. 4 per group):
+ *
+ *     ACC_g[m,n] = sum over the channels k of group g of q_a[m,k] * q_w[n,k]
+ *     Y[m,n]     = bf16( sw_n * ( sum_g ( s_mg ACC_g[m,n] + z_mg w_gsum[g,n] )
+ *                                 - zp_n * sum_g ( s_mg rowsum_mg + 128 z_mg ) ) + out_bias_n )
+ *
+ * which is sum_k x_hat[m,k] W_hat[n,k] + out_bias_n.  The integer products are exact; the sums over groups are
+ * fp32 multiply-adds in group order.
+ *   Aq, meta   as written by basq_rotate_quant with group_size = 128: [M, K/2] and [M, K/128] records
+ *   group_size must be 128 (else BASQ_EUNSUPPORTED); K % 128 == 0
+ *   Wq         uint8 [N, K/2] canonical;  w_scale, w_zero bf16 [N];  out_bias fp32 [N] or NULL
+ *   w_gsum     int32 [K/128, N], group-major: w_gsum[g*N + n] = sum of the codes of row n in group g
+ *              (basq_group_colsums)
+ *   Y          out, bf16 [M, ldy]
+ */
+int basq_w4a4_gemm_grouped(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, int32_t group_size,
+                           const uint8_t* Wq, int32_t N, const void* w_scale, const void* w_zero,
+                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy, void* stream);
+
+/* Offline: the per-group sums of the weight codes, w_gsum int32 [K/128, N] (see basq_w4a4_gemm_grouped). */
+int basq_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t group_size, int32_t* w_gsum, void* stream);
 
 /*
  * The fp6 operand form of an INT4 code matrix (device-side repacking; offline for weights).

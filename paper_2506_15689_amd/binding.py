@@ -22,7 +22,7 @@ BASQ_W_DECODE16 = 1
 STREAM_MAX_TOKENS = 128      # calls of at most this many tokens take the weight-streaming kernel (K % 128 == 0)
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
-           "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_w4a4_gemm_grouped", "basq_group_colsums", "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
            "basq_hadamard28", "basq_diag_stream", "basq_diag_read", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
@@ -54,6 +54,10 @@ def load() -> ctypes.CDLL:
     lib.basq_rotate_quant.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32, vp, vp, vp, vp, vp]
     lib.basq_w4a4_gemm.restype = c.c_int
     lib.basq_w4a4_gemm.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.basq_w4a4_gemm_grouped.restype = c.c_int
+    lib.basq_w4a4_gemm_grouped.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, i64, vp]
+    lib.basq_group_colsums.restype = c.c_int
+    lib.basq_group_colsums.argtypes = [vp, i32, i32, i32, vp, vp]
     lib.basq_fp6_bytes.restype = c.c_size_t
     lib.basq_fp6_bytes.argtypes = [i64, i32]
     lib.basq_pack_fp6.restype = c.c_int
@@ -145,6 +149,22 @@ def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_sca
     _check(load().basq_w4a4_gemm(_p(Aq), _p(meta), M, KB * 2, _p(Wq), N, w_layout, _p(w_scale), _p(w_zero),
                                  _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _p(acc_out),
                                  _p(Aq6), _p(Wq6), _stream(stream)))
+
+
+def basq_w4a4_gemm_grouped(Aq: torch.Tensor, meta: torch.Tensor, group_size: int, Wq: torch.Tensor, w_scale: torch.Tensor,
+                           w_zero: torch.Tensor, w_gsum: torch.Tensor, out_bias: Optional[torch.Tensor], Y: torch.Tensor,
+                           *, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Aq uint8 [M, K/2]; meta int32 [M*K/group_size, 4]; w_gsum int32 [K/group_size, N]."""
+    M, KB = Aq.shape
+    N = Wq.shape[0]
+    _check(load().basq_w4a4_gemm_grouped(_p(Aq), _p(meta), M, KB * 2, group_size, _p(Wq), N, _p(w_scale), _p(w_zero),
+                                         _p(w_gsum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _stream(stream)))
+
+
+def basq_group_colsums(Wq: torch.Tensor, group_size: int, w_gsum: torch.Tensor, *,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+    N, KB = Wq.shape
+    _check(load().basq_group_colsums(_p(Wq), N, KB * 2, group_size, _p(w_gsum), _stream(stream)))
 
 
 def basq_fp6_bytes(rows: int, K: int) -> int:

@@ -141,6 +141,31 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
     return run_gemm(g, static_cast<hipStream_t>(stream));
 }
 
+int basq_w4a4_gemm_grouped(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, int32_t group_size,
+                           const uint8_t* Wq, int32_t N, const void* w_scale, const void* w_zero,
+                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy, void* stream) {
+    const float dummy = 0.0f;   // validate_gemm wants the per-token weight sums, which this formula does not use
+    int rc = validate_gemm(Aq, meta, M, K, Wq, N, BASQ_W_CANONICAL, w_scale, w_zero, &dummy, Y, ldy);
+    if (rc != BASQ_OK) return rc;
+    if (group_size != 128) return fail(BASQ_EUNSUPPORTED, "group-wise GEMM: group_size must be 128 (got %d)", group_size);
+    if (K % 128 != 0) return fail(BASQ_EINVAL, "group-wise GEMM: K must be a multiple of 128 (got %d)", K);
+    if (!w_gsum) return fail(BASQ_EINVAL, "w_gsum is null");
+    if ((reinterpret_cast<uintptr_t>(w_gsum) & 3u) != 0) return fail(BASQ_EINVAL, "w_gsum must be 4-byte aligned");
+    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+               nullptr, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, nullptr, nullptr, BASQ_W_CANONICAL};
+    if (M > 0 && !gemm_grouped_applicable(g)) return fail(BASQ_EUNSUPPORTED, "group-wise GEMM: an operand exceeds 4 GiB");
+    return launch_gemm_grouped(g, w_gsum, static_cast<hipStream_t>(stream));
+}
+
+int basq_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t group_size, int32_t* w_gsum, void* stream) {
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (K <= 0 || K % 128 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 128 (got %d)", K);
+    if (group_size != 128) return fail(BASQ_EUNSUPPORTED, "group_size must be 128 (got %d)", group_size);
+    if (!Wq || !w_gsum) return fail(BASQ_EINVAL, "a pointer is null");
+    if (!aligned16(Wq)) return fail(BASQ_EINVAL, "Wq must be 16-byte aligned");
+    return launch_group_colsums(Wq, N, K, w_gsum, static_cast<hipStream_t>(stream));
+}
+
 size_t basq_workspace_bytes(int64_t M, int32_t K, int32_t N) {
     (void)N;
     if (M < 0 || K <= 0) return 0;

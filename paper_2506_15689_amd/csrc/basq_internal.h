@@ -65,6 +65,10 @@ int launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 // direct-to-LDS kernel for K % 256 == 0 (gemm_w4a4_direct.hip)
 bool gemm_direct_applicable(const GemmArgs& a);
 int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
+// activations quantised in groups of 128 channels (gemm_w4a4_grouped.hip); a.meta is [M, K/128]
+bool gemm_grouped_applicable(const GemmArgs& a);
+int launch_gemm_grouped(const GemmArgs& a, const int32_t* w_gsum, hipStream_t s);
+int launch_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t* out, hipStream_t s);
 constexpr int GEMV_MAX_TOKENS = 128;                          // above it the tiled GEMMs take over
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= GEMV_MAX_TOKENS, K % 128 == 0
 // one launch for the whole layer at decode size (linear_decode.hip)

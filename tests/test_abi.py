@@ -152,6 +152,17 @@ def test_decode_layout_sizes_and_argument_checks(lib):
                                  FAKE, FAKE, FAKE, None, FAKE, 32, None, ws, 1 << 30, None) == B.BASQ_EUNSUPPORTED
 
 
+def test_grouped_gemm_argument_checks(lib):
+    call = lambda M, K, G, gs=FAKE: lib.basq_w4a4_gemm_grouped(FAKE, FAKE, M, K, G, FAKE, 32, FAKE, FAKE, gs, None, FAKE, 32, None)
+    assert call(4, 256, 64) == B.BASQ_EUNSUPPORTED                     # only groups of 128
+    assert call(4, 192, 128) == B.BASQ_EINVAL                          # K % 128
+    assert call(4, 256, 128, None) == B.BASQ_EINVAL
+    assert call(0, 256, 128) == 0                                      # no tokens: nothing launched
+    assert lib.basq_group_colsums(FAKE, 8, 192, 128, FAKE, None) == B.BASQ_EINVAL
+    assert lib.basq_group_colsums(FAKE, 8, 256, 32, FAKE, None) == B.BASQ_EUNSUPPORTED
+    assert lib.basq_group_colsums(None, 8, 256, 128, FAKE, None) == B.BASQ_EINVAL
+
+
 def test_zero_tokens_is_valid_without_a_launch(lib):
     assert lib.basq_rotate_quant(None, 0, 1024, 1024, 1024, None, None, 0.9, 0.9, 4, 0, None, None, None, None, None) == 0
     assert lib.basq_w4a4_gemm(None, None, 0, 1024, FAKE, 16, 0, FAKE, FAKE, FAKE, None, None, 16, None, None, None, None) == 0

@@ -352,3 +352,74 @@ def test_per_head_kernel_variants():
 def test_groupwise_ranges_generic_kernel(K, rot, group):
     """Other group sizes, groups that differ from the rotation block, and a 28 * 2^t rotation."""
     run_group_case(37, K, rot, group, seed=K + group)
+
+
+# ---------------------------------------------------------------- group-wise ranges through the GEMM
+
+def run_grouped_layer(M, K, N, rot, *, seed=0, scale=False, odd_ldy=False):
+    """rotate+quant with group_size = 128, then basq_w4a4_gemm_grouped, against oracle.linear_grouped:
+    (i) codes and group records bit-exact on the GPU's rotation; group column sums bit-exact;
+    (ii) outputs: element by element within one bf16 step (2^-8 relative) plus 1e-5 of max|ref| of the oracle's
+    output on the same codes (the kernel sums the groups in fp32, the oracle in fp64), and within 2e-2 of
+    max|ref| of the oracle's output from X with its own rotation."""
+    announce(f"grouped layer M={M} K={K} N={N} rot={rot} scale={scale}")
+    dev = "cuda"
+    G = 128
+    lay = si.make_tiny(M, K, N, seed=seed, n_outlier=8, outlier_scale=20.0)
+    x = oracle.bf16_to_f32(si.bf16_bits(lay.X))
+    w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
+    wq = oracle.quantize_weights(w)
+    b = oracle.channel_bias(oracle.bf16_to_f32(si.bf16_bits(lay.X_calib)), rot)
+    sa = np.random.default_rng(seed + 5).uniform(0.8, 1.25, K).astype(np.float32) if scale else None
+    if sa is not None:
+        b = (b.astype(np.float64) * sa).astype(np.float32)
+    c = oracle.fused_bias(wq, b, None)
+    ng = K // G
+    X = lay.X.to(dev)
+    Aq = torch.zeros((M, K // 2), dtype=torch.uint8, device=dev)
+    meta = torch.zeros((M * ng, 4), dtype=torch.int32, device=dev)
+    rot_out = torch.empty((M, K), dtype=torch.float32, device=dev)
+    tb = torch.from_numpy(b).to(dev)
+    ts = None if sa is None else torch.from_numpy(sa).to(dev)
+    Wq = torch.from_numpy(oracle.pack_codes(wq.codes)).to(dev)
+    w_scale = si.bits_to_bf16(wq.scale_bits).to(dev)
+    w_zero = si.bits_to_bf16(wq.zero_bits).to(dev)
+    out_bias = torch.from_numpy(c).to(dev)
+    gsum = torch.full((ng, N), -1, dtype=torch.int32, device=dev)
+    ldy = N + 3 if odd_ldy else N
+    Ybuf = torch.full((M, ldy), float("nan"), dtype=torch.bfloat16, device=dev)
+    Y = Ybuf[:, :N]
+    B.basq_rotate_quant(X, rot, tb, ts, 0.9, 0.95, Aq, meta, rot_out, group_size=G)
+    B.basq_group_colsums(Wq, G, gsum)
+    B.basq_w4a4_gemm_grouped(Aq, meta, G, Wq, w_scale, w_zero, gsum, out_bias, Y)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gsum.cpu().numpy(), oracle.group_colsums(wq, G), err_msg="group column sums")
+    ref_i = oracle.linear_grouped(x, rot, b, sa, 0.9, 0.95, G, wq, c, r=rot_out.cpu().numpy())
+    np.testing.assert_array_equal(oracle.unpack_codes(Aq.cpu().numpy()), ref_i.tq.codes, err_msg="codes")
+    mh = meta.cpu().numpy().reshape(M, ng, 4)
+    np.testing.assert_array_equal(mh[:, :, 0].copy().view(np.uint32), ref_i.tq.scale.view(np.uint32))
+    np.testing.assert_array_equal(mh[:, :, 1].copy().view(np.uint32), ref_i.tq.lo.view(np.uint32))
+    np.testing.assert_array_equal(mh[:, :, 2], ref_i.tq.rowsum)
+    y = oracle.bf16_to_f32(si.bf16_bits(Y.cpu())).astype(np.float64)
+    assert np.isfinite(y).all()
+    top = float(np.abs(ref_i.y).max())
+    assert (np.abs(y - ref_i.y) <= 2.0 ** -8 * np.abs(ref_i.y) + 1e-5 * top).all(), \
+        f"worst {np.abs(y - ref_i.y).max() / top} of max|ref| on identical codes"
+    if odd_ldy:
+        assert torch.isnan(Ybuf[:, N:]).all(), "wrote past the row"
+    ref = oracle.linear_grouped(x, rot, b, sa, 0.9, 0.95, G, wq, c)
+    err = float(np.abs(y - ref.y).max() / np.abs(ref.y).max())
+    assert err <= pu.Y_TOL, f"output error {err}"
+    announce(f"ok y_err {err:.2e}")
+
+
+@pytest.mark.parametrize("M,K,N,rot", [(128, 128, 128, 128), (130, 256, 136, 128), (70, 1024, 200, 1024), (257, 512, 100, 128),
+                                       (5, 384, 17, 128), (300, 4096, 264, 4096)])
+def test_grouped_gemm(M, K, N, rot):
+    """Group-wise activation ranges through the GEMM: one, two, several and 32 groups; ragged tiles in both
+    directions; output widths that are no multiple of 8; per-head rotation (128) and full rotation."""
+    run_grouped_layer(M, K, N, rot, seed=M + N)
+
+
+def test_grouped_gemm_with_scale_and_unaligned_rows():
+    run_grouped_layer(140, 768, 72, 128, seed=9, scale=True, odd_ldy=True)
