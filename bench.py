@@ -125,8 +125,10 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = si.CONFIGS[args.config]
-    if (args.rot_size or args.group_size) and args.only != "rotate_quant":
-        print("bench.py: --rot-size and --group-size go with --only rotate_quant (the GEMM takes per-token ranges)", file=sys.stderr)
+    grouped = args.group_size == 128 and args.only != "rotate_quant"     # group-wise ranges through the GEMM
+    if (args.rot_size or args.group_size) and args.only != "rotate_quant" and not grouped:
+        print("bench.py: --rot-size and --group-size go with --only rotate_quant (the GEMM takes per-token ranges, "
+              "or groups of 128)", file=sys.stderr)
         sys.exit(2)
     rot_size = args.rot_size if args.rot_size > 0 else cfg.rot_size
     group = args.group_size
@@ -145,13 +147,17 @@ def main():
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
     use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > B.STREAM_MAX_TOKENS and group in (0, K)
+    w_gsum = None
+    if grouped:
+        w_gsum = torch.empty((K // 128, N), dtype=torch.int32, device=dev)
+        B.basq_group_colsums(Wq, 128, w_gsum)
     Wq6 = None
     if use_fp6:                                # offline: the weights once more in the fp6 operand form
         Wq6 = B.alloc_fp6_buffer(N, K, dev)
         B.basq_pack_fp6(Wq, Wq6)
     # decode shapes stream the weights once per call: the streaming layout (offline repack), and as many
     # distinct copies as it takes to keep them out of the 256 MB last-level cache between calls
-    decode = M <= B.STREAM_MAX_TOKENS and K % 128 == 0
+    decode = M <= B.STREAM_MAX_TOKENS and K % 128 == 0 and not grouped
     w_layout, wsets = B.BASQ_W_CANONICAL, [Wq]
     if decode:
         if args.weight_layout == "stream":
@@ -190,6 +196,9 @@ def main():
 
     def gemm(i):
         _, Aq, meta, Y, Aq6 = sets[i % nsets]
+        if grouped:
+            B.basq_w4a4_gemm_grouped(Aq, meta, 128, Wq, w_scale, w_zero, w_gsum, out_bias, Y, stream=stream)
+            return
         B.basq_w4a4_gemm(Aq, meta, wsets[i % len(wsets)], w_scale, w_zero, w_sum, out_bias, Y, None, Aq6=Aq6, Wq6=Wq6,
                          w_layout=w_layout, N=N, stream=stream)
 
@@ -200,6 +209,10 @@ def main():
     def step(i):
         """One pass of the whole hot path: the single fused entry point."""
         Xi, _, _, Y, _ = sets[i % nsets]
+        if grouped:                               # no one-call entry point for groups: the two calls
+            rotate_quant(i)
+            gemm(i)
+            return
         B.basq_linear_fused(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, wsets[i % len(wsets)], w_scale, w_zero,
                             w_sum, out_bias, Y, workspace, Wq6=Wq6, w_layout=w_layout, N=N, stream=stream)
 
@@ -306,7 +319,8 @@ def main():
         ach = ops / (gemm_ms * 1e-3) / 1e12
         peak = FP6_PEAK_TOPS if use_fp6 else INT8_PEAK_TOPS
         tkey = "gemm_fp6" if use_fp6 else "gemm"
-        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else "gemm_w4a4_direct_kernel", "bound": "mfma",
+        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else ("gemm_w4a4_grouped_kernel" if grouped else "gemm_w4a4_direct_kernel"),
+                "bound": "mfma",
                 "achieved": ach, "peak": peak, "unit": "TOP/s", "frac": ach / peak,
                 "traffic": MEASURED_TRAFFIC.get((args.config, tkey)), "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
         if use_fp6:
@@ -353,7 +367,7 @@ def main():
         "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,
     }
-    if not args.no_cpu_baseline and not rq_only:
+    if not args.no_cpu_baseline and not rq_only and not grouped:
         # about 1.5e12 integer operations keep the oracle busy for 10-30 s on the box's 16 host cores
         sample = max(1, min(M, int(round(1.5e12 / (2.0 * N * K)))))
         out["cpu_baseline"] = cpu_baseline(cfg, lay, sample)

@@ -134,11 +134,15 @@ struct P2Meta { float scale, lo; int rowsum; };
 // 8w + 2j, of ods[w] = code 8w + 2j + 1.
 // NC: 16-byte loads per lane per token (K = 512 * NC).  Without FOLD_NORM one fp32 multiply by `norm` follows
 // the butterflies.
-template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, class AfterMfma, class Sink>
+// GROUPED: one range per 128 consecutive channels instead of one per token (four neighbouring lanes own a group);
+// gsink(hf, b, scale, lo, rowsum) then receives the record of group 32*hf + 16*b + lane/4 (the same values on
+// the four lanes of the group) and the returned record is unused.
+template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED, class AfterMfma, class Sink,
+          class GroupSink>
 __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2], float* wl, const float4* lbias,
                                            const float* act_scale, float* rot_row, float norm, float clip_lo,
                                            float clip_hi, int lane, int wbase, int rbase, AfterMfma&& after_mfma,
-                                           Sink&& sink) {
+                                           Sink&& sink, GroupSink&& gsink) {
     constexpr int NH = NC / 8;                  // number of 4096-channel halves (bit 12)
     static_assert(NC == 8 || NC == 16, "K must be 4096 or 8192");
     // ---- first five stages on the matrix core ---------------------------------------------
@@ -222,10 +226,12 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
     // ---- normalise, bias, min/max ---------------------------------------------------------------
     // this lane owns channels e = 4096*hf + 2048*b + 32*lane + i
     float mn = INFINITY, mx = -INFINITY;
+    float gmn[NH][2], gmx[NH][2];                   // GROUPED: the ranges of this lane's 32-channel runs
 #pragma unroll
     for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
+            if (GROUPED) { mn = INFINITY; mx = -INFINITY; }
             const int e0 = 4096 * hf + 2048 * b + 32 * lane;
 #pragma unroll
             for (int i4 = 0; i4 < 8; ++i4) {
@@ -249,16 +255,24 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
                     *reinterpret_cast<float4*>(rot_row + e0 + 4 * i4) =
                         make_float4(rr[0], rr[1], rr[2], rr[3]);
             }
+            gmn[hf][b] = mn; gmx[hf][b] = mx;
         }
-    mn = wave_min_f(mn);
-    mx = wave_max_f(mx);
+    if (!GROUPED) {
+        mn = wave_min_f(mn);
+        mx = wave_max_f(mx);
+    }
 
-    const float lo = clip_lo * mn;
-    const float hi = clip_hi * mx;
-    float s = __fdiv_rn(hi - lo, 15.0f);
-    if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
-    const float inv = __fdiv_rn(1.0f, s);
-    const float nlo = -(lo * inv);
+    // per-token constants, or (GROUPED) those of group (hf, b, lane/4)
+    float lo, s, inv, nlo;
+    auto range_constants = [&](float vmin, float vmax) {
+        lo = clip_lo * vmin;
+        const float hi = clip_hi * vmax;
+        s = __fdiv_rn(hi - lo, 15.0f);
+        if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
+        inv = __fdiv_rn(1.0f, s);
+        nlo = -(lo * inv);
+    };
+    if (!GROUPED) range_constants(mn, mx);
 
     // ---- quantise, pack, store -----------------------------------------------------------------
     int sum = 0;
@@ -266,6 +280,13 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
     for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
+            if (GROUPED) {
+                float vmin = gmn[hf][b], vmax = gmx[hf][b];
+                vmin = fminf(vmin, dpp_f<DPP_QUAD_XOR1>(vmin)); vmin = fminf(vmin, dpp_f<DPP_QUAD_XOR2>(vmin));
+                vmax = fmaxf(vmax, dpp_f<DPP_QUAD_XOR1>(vmax)); vmax = fmaxf(vmax, dpp_f<DPP_QUAD_XOR2>(vmax));
+                range_constants(vmin, vmax);
+                sum = 0;
+            }
             uint32_t words[4], evs[4], ods[4];
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
@@ -283,8 +304,13 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
                 evs[w] = ev; ods[w] = od;
             }
             sink(hf, b, words, evs, ods);
+            if (GROUPED) {
+                sum += dpp_i<DPP_QUAD_XOR1>(sum);
+                sum += dpp_i<DPP_QUAD_XOR2>(sum);
+                gsink(hf, b, s, lo, sum);
+            }
         }
-    sum = wave_sum_i(sum);
+    if (!GROUPED) sum = wave_sum_i(sum);
     P2Meta out;
     out.scale = s; out.lo = lo; out.rowsum = sum;
     return out;

@@ -21,7 +21,8 @@ constexpr int P2_THREADS = P2_WAVES * 64;
 
 // NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
 // sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
-template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
+// GROUPED: one range and one record per 128 channels (group_size = 128) instead of per token.
+template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED>
 __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
     constexpr int K = 512 * NC;
     constexpr bool PREFETCH = (NC == 8) && P2_PREFETCH;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     for (; m < a.M; m += wave_stride) {
         if (!PREFETCH) load_token(m);
         const int64_t mnext = m + wave_stride;
-        const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, ROT_OUT>(
+        const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, ROT_OUT, GROUPED>(
             raw, bop, wl, lbias, a.act_scale, ROT_OUT ? a.rot_out + m * (int64_t)K : nullptr, norm, a.clip_lo, a.clip_hi,
             lane, pl.wbase, pl.rbase,
             // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
@@ -91,8 +92,15 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                         make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
                     *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
                 }
+            },
+            [&](int hf, int b, float gs, float glo, int gsum) {
+                if ((lane & 3) == 0) {
+                    basq_tokmeta mt;
+                    mt.scale = gs; mt.lo = glo; mt.rowsum = gsum; mt.reserved = 0;
+                    a.meta[m * (K / 128) + 32 * hf + 16 * b + (lane >> 2)] = mt;
+                }
             });
-        if (lane == 0) {
+        if (!GROUPED && lane == 0) {
             basq_tokmeta mt;
             mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum; mt.reserved = 0;
             a.meta[m] = mt;
@@ -102,10 +110,15 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
 
 template <int NC, bool FOLD, bool HB, bool HS>
 int launch_flags(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm) {
-    if (a.rot_out)
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+    const bool grouped = a.group != a.K;
+    if (a.rot_out && grouped)
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+    else if (grouped)
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+    else if (a.rot_out)
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
     else
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
     return check_hip(hipGetLastError(), "rotate_quant (pow2) launch");
 }
 
@@ -121,7 +134,9 @@ int launch_nc(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float no
 }  // namespace
 
 bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
-    return a.group == a.K && !a.has28 && a.rot_size == a.K && (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
+    // per-token ranges, or groups of 128 channels (four neighbouring lanes; no fp6 copy: the GEMM that takes it is per token)
+    return (a.group == a.K || (a.group == 128 && a.Aq6 == nullptr)) && !a.has28 && a.rot_size == a.K &&
+           (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
 }
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {

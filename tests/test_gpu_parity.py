@@ -342,6 +342,13 @@ def test_per_head_kernel(M, K):
     run_group_case(M, K, 128, 128, seed=K + M)
 
 
+@pytest.mark.parametrize("M,K,scale,bias", [(9, 4096, False, True), (70, 8192, False, True), (6, 4096, True, True), (5, 8192, True, False)])
+def test_full_rotation_with_groups_of_128(M, K, scale, bias):
+    """rot_size = K in {4096, 8192} with group_size = 128: the one-wave-per-token kernel with one range per four
+    neighbouring lanes."""
+    run_group_case(M, K, K, 128, seed=K + M, scale=scale, bias=bias)
+
+
 def test_per_head_kernel_variants():
     run_group_case(40, 4096, 128, 128, seed=1, scale=True)
     run_group_case(40, 1024, 128, 128, seed=2, bias=False, clip_lo=1.0, clip_hi=1.0)
