@@ -380,9 +380,13 @@ int launch_gemm_fp6(const GemmArgs& a, hipStream_t s) {
     return launch_fp6<GEMM_FP6_CFG>(a, s);
 #else
     auto tiles = [&](int bm, int bn) { return ((a.M + bm - 1) / bm) * (((int64_t)a.N + bn - 1) / bn); };
+    // Three tilings, chosen by how evenly their tiles fill the 256 compute units, weighted by the per-tile rate
+    // measured against the square 256 tile (256 x 192: wave tiles of 64 x 96, 0.90; 128 x 128: 0.85)
     const double s_big = 1.00 * round_efficiency6(tiles(256, 256), 256);
+    const double s_mid = 0.90 * round_efficiency6(tiles(256, 192), 256);
     const double s_small = 0.85 * round_efficiency6(tiles(128, 128), 512);
-    if (s_big >= s_small) return launch_fp6<256, 256, 2, 4, 3, 2>(a, s);
+    if (s_big >= s_mid && s_big >= s_small) return launch_fp6<256, 256, 2, 4, 3, 2>(a, s);
+    if (s_mid >= s_small) return launch_fp6<256, 192, 4, 2, 3, 2>(a, s);
     return launch_fp6<128, 128, 2, 2, 3, 2>(a, s);
 #endif
 }

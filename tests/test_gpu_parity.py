@@ -41,7 +41,7 @@ def test_c1_full():
     run_case(si.make_layer(si.CONFIGS["C1"]))
 
 
-@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (161, 256, 40), (129, 4096, 96)])
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (161, 256, 40), (129, 4096, 96), (200, 512, 1152), (260, 1024, 1100)])
 def test_ragged_multi_tile(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=M))
 
