@@ -117,6 +117,9 @@ def main():
     from paper_2506_15689_amd import binding as B
     from paper_2506_15689_amd import synth_inputs as si
 
+    if args.config not in si.CONFIGS:
+        print(f"bench.py: unknown workload {args.config!r}; known: {', '.join(sorted(si.CONFIGS))}", file=sys.stderr)
+        sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
