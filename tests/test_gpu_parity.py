@@ -430,3 +430,56 @@ def test_grouped_gemm(M, K, N, rot):
 
 def test_grouped_gemm_with_scale_and_unaligned_rows():
     run_grouped_layer(140, 768, 72, 128, seed=9, scale=True, odd_ldy=True)
+
+
+# ---------------------------------------------------------------- HIP graph capture
+
+@pytest.mark.parametrize("M,K,N,stream_layout", [(1, 4096, 4096, True), (16, 4096, 256, True), (40, 1024, 200, False), (200, 512, 136, False)])
+def test_calls_can_be_captured_in_a_graph(M, K, N, stream_layout):
+    """Hot calls allocate nothing, never synchronise and launch only kernels, so a serving loop may record them in a
+    HIP graph: four layer calls are captured once and replayed three times, with eager work and synchronisations in
+    between and fresh inputs before every replay; every replay must reproduce the eager call's bits."""
+    dev = torch.device("cuda")
+    lay = si.make_tiny(M, K, N, seed=M + N)
+    case = pu.make_case(lay)
+    d = pu.to_device(case)
+    Wq, layout = d.Wq, B.BASQ_W_CANONICAL
+    if stream_layout:
+        Wq = torch.empty(B.basq_decode_bytes(N, K), dtype=torch.uint8, device=dev)
+        B.basq_pack_decode(d.Wq, Wq)
+        layout = B.BASQ_W_DECODE16
+    W6 = None
+    if M > B.STREAM_MAX_TOKENS:
+        W6 = B.alloc_fp6_buffer(N, K, dev)
+        B.basq_pack_fp6(d.Wq, W6)
+    ws = torch.empty(max(B.basq_workspace_bytes(M, K, N), 256), dtype=torch.uint8, device=dev)
+    X = [d.X.clone() for _ in range(4)]
+    Y = [torch.empty((M, N), dtype=torch.bfloat16, device=dev) for _ in range(4)]
+
+    def layer(i, stream=None):
+        B.basq_linear_fused(X[i], case.rot_size, d.bias, d.act_scale, case.clip_lo, case.clip_hi, Wq, d.w_scale, d.w_zero,
+                            d.w_sum, d.out_bias, Y[i], ws, Wq6=W6, w_layout=layout, N=N, stream=stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for i in range(4):
+            layer(i)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    for rep in range(3):
+        for i in range(4):                               # new tokens in the captured buffers
+            X[i].copy_((torch.randn((M, K), generator=gen) * (1.0 + rep)).to(torch.bfloat16))
+            Y[i].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [y.clone() for y in Y]
+        for i in range(4):                               # the same calls, eagerly
+            Y[i].fill_(float("nan"))
+            layer(i)
+        torch.cuda.synchronize()
+        for i in range(4):
+            assert not torch.isnan(got[i].float()).any()
+            assert torch.equal(got[i], Y[i]), f"replay {rep}, call {i}"
