@@ -60,6 +60,9 @@ def parse_args():
                         "or on the int8 path; decode-sized M always streams the INT4 weights")
     p.add_argument("--weight-layout", default="stream", choices=["stream", "canonical"],
                    help="decode shapes (M <= 128): weights in the weight-streaming layout (default) or canonical")
+    p.add_argument("--graph", action="store_true",
+                   help="record the K timed steps in one HIP graph and time its replay (decode shapes: removes the host's "
+                        "launch cost of a few microseconds per call from the measurement)")
     p.add_argument("--rot-size", type=int, default=0, help="with --only rotate_quant: rotation block instead of the workload's")
     p.add_argument("--group-size", type=int, default=0,
                    help="with --only rotate_quant: channels per range (0 = per token); 128 with --rot-size 128 is the "
@@ -246,6 +249,26 @@ def main():
     # that each kernel's average duration is known (events around every single launch would add
     # several microseconds of their own to kernels this short)
     _, ms_step = timed(whole, args.steps)
+    if args.graph:
+        # the same K steps, recorded once on a capture stream and replayed: the device-side time of the step
+        cap = torch.cuda.Stream()
+        cap.wait_stream(stream)
+        g = torch.cuda.CUDAGraph()
+        eager_stream = stream
+        with torch.cuda.graph(g, stream=cap):
+            stream = torch.cuda.current_stream()
+            for i in range(args.steps):
+                whole(i)
+        stream = eager_stream
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms_step_eager, ms_step = ms_step, e0.elapsed_time(e1) / args.steps
     rq_ms, _ = timed(rotate_quant, args.steps)
     gemm_ms = float("nan") if rq_only else timed(gemm, args.steps)[0]
     gemm_int8_ms = timed(gemm_int8, args.steps)[0] if use_fp6 and not rq_only else None
@@ -363,6 +386,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": rot_size, "group_size": group if group else K,
                    "clip": cfg.clip, "buffer_sets": nsets, "weight_copies": len(wsets),
                    "weight_layout": "streaming (16-row blocks)" if w_layout == B.BASQ_W_DECODE16 else "canonical",
+                   "launch": "HIP graph replay of the K steps" if args.graph else "eager",
                    "step_launches": 1 if (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192)
                                           and rot_size == K) else 2,
                    "matrix_path": "fp6" if use_fp6 else ("int4 weight streaming" if decode else "int8")},
