@@ -4,6 +4,7 @@
 // the epilogue (paper Sec. 5.2; Fig. 6; Eq. 14).  Same arithmetic and nibble split as
 // gemm_w4a4.hip, which remains the fallback for K % 128 != 0.
 #include "basq_internal.h"
+#include <type_traits>
 
 namespace basq {
 
@@ -160,7 +161,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
     static_assert((NCH / 2) % 2 == 0, "the two fragment register sets alternate per h");
     read_frags(lds, 0, 0);
 
-    for (int ks = 0; ks < ksteps; ++ks) {
+    // One K-step; the last one is peeled off the loop so that "is there a next stage to read" is known at compile
+    // time: otherwise two paths meet in front of the last block of MFMAs, one without the next stage's reads in
+    // flight, and the compiler waits there for every outstanding LDS read instead of only the operands in use.
+    auto k_step = [&](int ks, auto has_next) {
         const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
         // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
         if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
@@ -172,13 +176,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_dire
                 // last h of the step: every read of this stage has been issued and consumed; pass the
                 // barrier (next stage complete and visible), then start the next step's first reads
                 if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<LOADS>(); else wait_loads_and_barrier<0>();
-                if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
+                if (decltype(has_next)::value) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
             compute(h & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    };
+    int ks = 0;
+    for (; ks + 1 < ksteps; ++ks) k_step(ks, std::true_type{});
+    k_step(ks, std::false_type{});
     __syncthreads();
 
     // ---- epilogue: row and column constants through LDS (free now), then one bf16 per lane per store

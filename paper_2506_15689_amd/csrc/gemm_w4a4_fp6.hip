@@ -11,6 +11,7 @@
 // fp6_pack.hip): a stage is filled by contiguous 1 KB copies of whole cache lines, and both the 16-byte
 // and the 8-byte fragment reads are free of bank conflicts.  No unpacking: LDS -> registers -> MFMA.
 #include "basq_internal.h"
+#include <type_traits>
 
 namespace basq {
 
@@ -113,8 +114,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         const unsigned koff_a = (unsigned)ks * a_step, koff_w = (unsigned)ks * w_step;   // unsigned 32-bit byte offsets
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            if (i * WAVES + swave >= PIECES) continue;           // (uniform over the wave, like the next test)
-            if (i * WAVES + swave < A_PIECES)
+            // which operand a piece belongs to, and whether it exists, is known at compile time when the pieces
+            // divide evenly over the waves (no branch per load then); otherwise it depends on the wave (uniform)
+            constexpr bool EVEN = PIECES % WAVES == 0 && A_PIECES % WAVES == 0;
+            if (!EVEN && i * WAVES + swave >= PIECES) continue;
+            if (EVEN ? i < A_PIECES / WAVES : i * WAVES + swave < A_PIECES)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_a + (unsigned)soff[i]), 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_w + (unsigned)soff[i]), 0, 0);
@@ -214,7 +218,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         first = false;
         read_frags(lds, 0, 0);
 
-        for (int ks = 0; ks < ksteps; ++ks) {
+        // One K-step.  The last one is peeled off the loop: with the "is there a next stage to read" test inside the
+        // loop, two paths meet in front of the second block of MFMAs, one of them without the reads of the next
+        // stage in flight, and the compiler then waits for every outstanding LDS read there -- including the ones
+        // just issued -- instead of only for the operands the MFMAs use (a bubble of an LDS latency per step).
+        auto k_step = [&](int ks, auto has_next) {
             const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
             // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
             if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
@@ -226,11 +234,14 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
             // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
             // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
             if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<MIN_LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
-            if (ks + 1 < ksteps) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
+            if (decltype(has_next)::value) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             compute(1);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+        int ks = 0;
+        for (; ks + 1 < ksteps; ++ks) k_step(ks, std::true_type{});
+        k_step(ks, std::false_type{});
         // every wave has passed the last step's barrier, after which nothing reads the ring: request the
         // next tile's first stages now, so that their latency hides behind this tile's epilogue
         const int next_pid = pid + gridDim.x;
