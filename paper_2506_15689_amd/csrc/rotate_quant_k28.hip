@@ -69,6 +69,7 @@ __device__ __forceinline__ void lds_barrier() {
 
 template <int K28_WAVES, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT>
 __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k28_kernel(RotateQuantArgs a, float norm, H28Cols hc) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the body uses device-only buffer-resource types; the host pass only needs the stub
     // bias (and s^a) laid out so that for a piece index q the 64 lanes of a wave half read consecutive float4s
     constexpr int K28_THREADS = K28_WAVES * 64;
     constexpr int VEC_WORDS = 2 * 32 * 64 * 4;
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
     __shared__ __attribute__((aligned(16))) float lds[BIAS_WORDS + SCALE_WORDS + 64];
     float* red = lds + BIAS_WORDS + SCALE_WORDS;   // [parity][token in block][half][mn, mx, sum, -]
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int half = wave & 1, tok_in_blk = wave >> 1;
     const int g = lane >> 4, m16 = lane & 15;
     const int ip = 16 * half + m16;                // output row i'
@@ -115,14 +116,16 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         bop = __builtin_bit_cast(v8bf, tmp);
     }
 
-    // 16-byte loads of column block jb of a token: rows 8g .. 8g+7 (rows >= 28 read as zero)
+    // 16-byte loads of column block jb of a token: rows 8g .. 8g+7.  Buffer loads on a descriptor that ends with
+    // the token: rows >= 28 lie past its end and read as zero without a branch -- with a branch per row the paths
+    // that meet afterwards carry different numbers of loads in flight and every wait becomes a wait for all of them,
+    // the prefetched block of the next token included.  `tok` is uniform over the wave.
     auto load_block = [&](v4u (&R)[8], int64_t tok, int jb) {
-        const uint16_t* xrow = a.X + tok * a.ldx + 8 * m16 + 128 * jb;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.X + tok * a.ldx), 0, K28 * 2, 0x00020000);
+        const int voff = 8192 * g + 16 * m16 + 256 * jb;                 // bytes; row i = 8g + t starts at 1024 i
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int i = 8 * g + t;
-            R[t] = (i < 28) ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(xrow + i * 512)) : v4u{0u, 0u, 0u, 0u};
-        }
+        for (int t = 0; t < 8; ++t)
+            R[t] = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 1024 * t, 0, 2 /* non-temporal */));
     };
 
     // Workgroups g, g+8, ... share an XCD; renumbered so that an XCD owns a contiguous range, 32
@@ -359,6 +362,7 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         mt.reserved = 0;
         a.meta[prev_m] = mt;
     }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 template <bool HB, bool HS>
