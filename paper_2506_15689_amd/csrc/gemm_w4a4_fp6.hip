@@ -114,11 +114,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         const unsigned koff_a = (unsigned)ks * a_step, koff_w = (unsigned)ks * w_step;   // unsigned 32-bit byte offsets
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            // which operand a piece belongs to, and whether it exists, is known at compile time when the pieces
-            // divide evenly over the waves (no branch per load then); otherwise it depends on the wave (uniform)
-            constexpr bool EVEN = PIECES % WAVES == 0 && A_PIECES % WAVES == 0;
-            if (!EVEN && i * WAVES + swave >= PIECES) continue;
-            if (EVEN ? i < A_PIECES / WAVES : i * WAVES + swave < A_PIECES)
+            // whether piece i * WAVES + wave exists is known at compile time for all but a last partial round, and
+            // which operand it belongs to whenever the activation pieces fill whole rounds: no branch per load then
+            // (the wave-dependent tests are uniform over the wave)
+            if ((i + 1) * WAVES > PIECES && i * WAVES + swave >= PIECES) continue;
+            if (A_PIECES % WAVES == 0 ? i < A_PIECES / WAVES : i * WAVES + swave < A_PIECES)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_a + (unsigned)soff[i]), 0, 0);
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_w, LDS_PTR(stage + i * WAVES * 1024), 16, lane_off, (int)(koff_w + (unsigned)soff[i]), 0, 0);
