@@ -33,9 +33,9 @@ FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
 # HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
 # under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
 MEASURED_TRAFFIC = {
-    ("C2", "rotate_quant"): 27570123, ("C2", "gemm"): 170395618, ("C2", "gemm_fp6"): 176981333,
-    ("C4", "rotate_quant"): 105886152, ("C4", "gemm"): 173447739, ("C4", "gemm_fp6"): 240621211,
-    ("C5", "rotate_quant"): 109639834, ("C5", "gemm"): 944411931, ("C5", "gemm_fp6"): 1294334652,
+    ("C2", "rotate_quant"): 27568891, ("C2", "gemm"): 169999751, ("C2", "gemm_fp6"): 176946203,
+    ("C4", "rotate_quant"): 108649851, ("C4", "gemm"): 176765487, ("C4", "gemm_fp6"): 260375205,
+    ("C5", "rotate_quant"): 109642653, ("C5", "gemm"): 945049926, ("C5", "gemm_fp6"): 1294326691,
     ("C3_M16", "rotate_quant"): 301233, ("C3_M16", "gemm"): 8985923,
     ("C3_M1", "rotate_quant"): 44642, ("C3_M1", "gemm"): 8616106,
 }
