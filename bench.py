@@ -289,16 +289,17 @@ def main():
     ceilings = {}
     if not args.no_ceilings:
         ct = max(M, 32768)                                  # enough tokens to reach the streaming asymptote
-        csrc = torch.empty(ct * 2 * K, dtype=torch.uint8, device=dev).fill_(1)
-        cdst = torch.empty(ct * (K // 2), dtype=torch.uint8, device=dev)
+        ck = (K + 2047) // 2048 * 2048                      # the streaming kernel moves whole 2048-channel pieces
+        csrc = torch.empty(ct * 2 * ck, dtype=torch.uint8, device=dev).fill_(1)
+        cdst = torch.empty(ct * (ck // 2), dtype=torch.uint8, device=dev)
         cmeta = torch.empty(ct * 16, dtype=torch.uint8, device=dev)
 
         def stream_once(i):
-            B.basq_diag_stream(csrc, cdst, cmeta, ct, K, stream=stream)
+            B.basq_diag_stream(csrc, cdst, cmeta, ct, ck, stream=stream)
         for i in range(3):
             stream_once(i)
         ms, _ = timed(stream_once, 10)
-        ceilings["hbm_stream_GBps"] = ct * (2 * K + K // 2 + 16) / (ms * 1e-3) / 1e9
+        ceilings["hbm_stream_GBps"] = ct * (2 * ck + ck // 2 + 16) / (ms * 1e-3) / 1e9
         del csrc, cdst, cmeta
         cout = torch.empty(512 * 256, dtype=torch.int32, device=dev)
         iters = 2000
