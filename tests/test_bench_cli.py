@@ -33,3 +33,28 @@ def test_algorithmic_bytes_follow_the_stated_formulas():
     assert bench.algorithmic_bytes_rotate_quant(M, K, False, 128) == M * (2 * K + K // 2 + 16 * (K // 128))
     # decode-sized product: the weights once, their three vectors, the codes, records and the output
     assert bench.algorithmic_bytes_gemm(16, 4096, 4096, False) == 4096 * 2048 + 4096 * 12 + 16 * (2048 + 16) + 2 * 16 * 4096
+
+
+import json
+
+import pytest
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("args", [["--config", "C1"], ["--config", "C3_M4"], ["--config", "C1", "--group-size", "128"],
+                                  ["--config", "C1", "--only", "rotate_quant", "--rot-size", "128", "--group-size", "128"],
+                                  ["--config", "C3_M1", "--graph"]])
+def test_bench_prints_one_json_line_with_the_contract_fields(args):
+    p = run_bench("--steps", "3", "--warmup", "1", "--no-cpu-baseline", *args)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["data"] == "synthetic" and "workload" in d["config"]
+    r = d["roofline"]
+    for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert key in r, key
+    assert r["bound"] in ("hbm", "mfma") and 0.0 < r["frac"] < 1.0 and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
