@@ -190,8 +190,11 @@ size_t basq_workspace_bytes(int64_t M, int32_t K, int32_t N);
 /*
  * The whole layer in one call: basq_rotate_quant then basq_w4a4_gemm on `stream`, the codes and
  * token records living in `workspace` (256-byte aligned, >= basq_workspace_bytes(M, K, N), else
- * BASQ_EWORKSPACE).  Arguments as in the two calls above; with Wq6 a prefill-sized M takes the fp6
- * matrix-core path.
+ * BASQ_EWORKSPACE).  Arguments as in the two calls above; with Wq6, M > 128 takes the fp6 matrix-core path.
+ * group_size must be 0 or K here (BASQ_EUNSUPPORTED otherwise: groups go through basq_rotate_quant and
+ * basq_w4a4_gemm_grouped).  With at most 4 tokens, rot_size == K in {4096, 8192}, N <= 4096 and
+ * w_layout = BASQ_W_DECODE16 the whole layer is one kernel launch (same results bit for bit).  Nothing in this
+ * call allocates or synchronises, so it may be recorded in a HIP graph.
  */
 int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
                       const float* bias, const float* act_scale,
