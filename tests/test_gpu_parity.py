@@ -53,6 +53,14 @@ def test_short_k_on_the_fp6_path(M, K, N):
     run_case(si.make_tiny(M, K, N, seed=K + M), rot_size=128)
 
 
+@pytest.mark.parametrize("M,K,N", [(150, 32768, 40), (20, 32768, 24), (140, 28 * 1024, 40), (133, 16384, 72)])
+def test_largest_supported_k(M, K, N):
+    """K = 32768 is the longest token the library accepts (the generic rotation holds it in 128 KB of LDS, the fp6
+    accumulator is exact up to there); 28 * 1024 is the longest Kronecker size below it, and 16384 the first size whose
+    token needs more than the default 64 KB of LDS."""
+    run_case(si.make_tiny(M, K, N, seed=K // 1024 + M))
+
+
 @pytest.mark.parametrize("K,rot", [(1024, 128), (512, 64), (256, 32), (64, 2)])
 def test_blockwise_rotation(K, rot):
     run_case(si.make_tiny(48, K, 64, seed=K + rot), rot_size=rot)
