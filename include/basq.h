@@ -140,10 +140,14 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
  *   w_gsum     int32 [K/128, N], group-major: w_gsum[g*N + n] = sum of the codes of row n in group g
  *              (basq_group_colsums)
  *   Y          out, bf16 [M, ldy]
+ *   Aq6, Wq6   optional, both or neither: the same codes in the fp6 operand form (basq_rotate_quant's Aq6 output or
+ *              basq_pack_fp6; basq_fp6_bytes each).  With them the product runs on the f8f6f4 matrix cores, about
+ *              1.5 times as fast, with bit-identical Y.
  */
 int basq_w4a4_gemm_grouped(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, int32_t group_size,
                            const uint8_t* Wq, int32_t N, const void* w_scale, const void* w_zero,
-                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy, void* stream);
+                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy,
+                           const uint8_t* Aq6, const uint8_t* Wq6, void* stream);
 
 /* Offline: the per-group sums of the weight codes, w_gsum int32 [K/128, N] (see basq_w4a4_gemm_grouped). */
 int basq_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t group_size, int32_t* w_gsum, void* stream);

@@ -55,7 +55,7 @@ def load() -> ctypes.CDLL:
     lib.basq_w4a4_gemm.restype = c.c_int
     lib.basq_w4a4_gemm.argtypes = [vp, vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.basq_w4a4_gemm_grouped.restype = c.c_int
-    lib.basq_w4a4_gemm_grouped.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, i64, vp]
+    lib.basq_w4a4_gemm_grouped.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.basq_group_colsums.restype = c.c_int
     lib.basq_group_colsums.argtypes = [vp, i32, i32, i32, vp, vp]
     lib.basq_fp6_bytes.restype = c.c_size_t
@@ -153,12 +153,15 @@ def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_sca
 
 def basq_w4a4_gemm_grouped(Aq: torch.Tensor, meta: torch.Tensor, group_size: int, Wq: torch.Tensor, w_scale: torch.Tensor,
                            w_zero: torch.Tensor, w_gsum: torch.Tensor, out_bias: Optional[torch.Tensor], Y: torch.Tensor,
-                           *, stream: Optional[torch.cuda.Stream] = None) -> None:
-    """Aq uint8 [M, K/2]; meta int32 [M*K/group_size, 4]; w_gsum int32 [K/group_size, N]."""
+                           *, Aq6: Optional[torch.Tensor] = None, Wq6: Optional[torch.Tensor] = None,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Aq uint8 [M, K/2]; meta int32 [M*K/group_size, 4]; w_gsum int32 [K/group_size, N]; Aq6/Wq6: the fp6 operand
+    forms (both or neither)."""
     M, KB = Aq.shape
     N = Wq.shape[0]
     _check(load().basq_w4a4_gemm_grouped(_p(Aq), _p(meta), M, KB * 2, group_size, _p(Wq), N, _p(w_scale), _p(w_zero),
-                                         _p(w_gsum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _stream(stream)))
+                                         _p(w_gsum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
+                                         _p(Aq6), _p(Wq6), _stream(stream)))
 
 
 def basq_group_colsums(Wq: torch.Tensor, group_size: int, w_gsum: torch.Tensor, *,

@@ -118,8 +118,6 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     if (!aligned16(Aq) || !aligned16(meta) || !aligned16(rot_out) || !aligned16(Aq6))
         return fail(BASQ_EINVAL, "Aq, meta, rot_out and Aq6 must be 16-byte aligned");
     if (Aq6 && K % 128 != 0) return fail(BASQ_EINVAL, "the fp6 operand form needs K %% 128 == 0 (got %d)", K);
-    if (Aq6 && group_size != 0 && group_size != K)
-        return fail(BASQ_EINVAL, "the fp6 operand form is the GEMM's, which takes per-token ranges only");
     a.X = static_cast<const uint16_t*>(X);
     a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
     a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
@@ -143,7 +141,8 @@ int basq_w4a4_gemm(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32
 
 int basq_w4a4_gemm_grouped(const uint8_t* Aq, const basq_tokmeta* meta, int64_t M, int32_t K, int32_t group_size,
                            const uint8_t* Wq, int32_t N, const void* w_scale, const void* w_zero,
-                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy, void* stream) {
+                           const int32_t* w_gsum, const float* out_bias, void* Y, int64_t ldy,
+                           const uint8_t* Aq6, const uint8_t* Wq6, void* stream) {
     const float dummy = 0.0f;   // validate_gemm wants the per-token weight sums, which this formula does not use
     int rc = validate_gemm(Aq, meta, M, K, Wq, N, BASQ_W_CANONICAL, w_scale, w_zero, &dummy, Y, ldy);
     if (rc != BASQ_OK) return rc;
@@ -151,8 +150,11 @@ int basq_w4a4_gemm_grouped(const uint8_t* Aq, const basq_tokmeta* meta, int64_t 
     if (K % 128 != 0) return fail(BASQ_EINVAL, "group-wise GEMM: K must be a multiple of 128 (got %d)", K);
     if (!w_gsum) return fail(BASQ_EINVAL, "w_gsum is null");
     if ((reinterpret_cast<uintptr_t>(w_gsum) & 3u) != 0) return fail(BASQ_EINVAL, "w_gsum must be 4-byte aligned");
+    rc = validate_fp6(Aq6, Wq6, true, K);
+    if (rc != BASQ_OK) return rc;
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               nullptr, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, nullptr, nullptr, BASQ_W_CANONICAL};
+               nullptr, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Wq6, BASQ_W_CANONICAL};
+    if (M > 0 && gemm_grouped_fp6_applicable(g)) return launch_gemm_grouped_fp6(g, w_gsum, static_cast<hipStream_t>(stream));
     if (M > 0 && !gemm_grouped_applicable(g)) return fail(BASQ_EUNSUPPORTED, "group-wise GEMM: an operand exceeds 4 GiB");
     return launch_gemm_grouped(g, w_gsum, static_cast<hipStream_t>(stream));
 }

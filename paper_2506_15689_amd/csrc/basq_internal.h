@@ -69,6 +69,9 @@ int launch_gemm_direct(const GemmArgs& a, hipStream_t s);
 bool gemm_grouped_applicable(const GemmArgs& a);
 int launch_gemm_grouped(const GemmArgs& a, const int32_t* w_gsum, hipStream_t s);
 int launch_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t* out, hipStream_t s);
+// the same product on the f8f6f4 matrix-core path: a.Aq6 / a.Wq6 in the fp6 operand form (gemm_w4a4_grouped_fp6.hip)
+bool gemm_grouped_fp6_applicable(const GemmArgs& a);
+int launch_gemm_grouped_fp6(const GemmArgs& a, const int32_t* w_gsum, hipStream_t s);
 constexpr int GEMV_MAX_TOKENS = 128;                          // above it the tiled GEMMs take over
 int launch_gemv_decode(const GemmArgs& a, hipStream_t s);   // M <= GEMV_MAX_TOKENS, K % 128 == 0
 // one launch for the whole layer at decode size (linear_decode.hip)

@@ -21,6 +21,7 @@ namespace basq {
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -196,10 +197,13 @@ __global__ __launch_bounds__(GG_THREADS, 2) void gemm_w4a4_grouped_kernel(GemmAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
-                const float2 sz = *reinterpret_cast<const float2*>(slot + (wm * GG_WM + i * 32 + rloc) * 16);   // scale, lo
+                // read as integers: the compiler puts a wait for every outstanding direct-to-LDS load in front of a
+                // float-typed LDS read, which would drain the ring in every step
+                const v2i szb = *reinterpret_cast<const v2i*>(slot + (wm * GG_WM + i * 32 + rloc) * 16);   // scale, lo
+                const float sc = __int_as_float(szb[0]), lo = __int_as_float(szb[1]);
 #pragma unroll
                 for (int j = 0; j < GG_TN; ++j)
-                    facc[i][j][r] = fmaf(sz.x, (float)acc[i][j][r], fmaf(sz.y, cs[j], facc[i][j][r]));
+                    facc[i][j][r] = fmaf(sc, (float)acc[i][j][r], fmaf(lo, cs[j], facc[i][j][r]));
             }
     }
     __syncthreads();

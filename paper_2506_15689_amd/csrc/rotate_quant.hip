@@ -230,6 +230,14 @@ int launch_rotate_quant_generic(const RotateQuantArgs& a, hipStream_t s);
 
 int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     if (a.M == 0) return BASQ_OK;
+    if (a.Aq6 && a.group != a.K) {
+        // group-wise ranges: the codes are the same kind of data, the fp6 copy is made from them afterwards
+        RotateQuantArgs b = a;
+        b.Aq6 = nullptr;
+        const int rc = launch_rotate_quant(b, s);
+        if (rc != BASQ_OK || !a.Aq) return rc;
+        return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);
+    }
     // the two specialised kernels write the fp6 copy of the codes themselves
     if (rotate_quant_pow2_applicable(a)) return launch_rotate_quant_pow2(a, s);
     if (rotate_quant_k28_applicable(a)) return launch_rotate_quant_k28(a, s);

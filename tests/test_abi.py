@@ -55,7 +55,7 @@ FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fa
     (dict(bits=3), B.BASQ_EUNSUPPORTED),
     (dict(group=100), B.BASQ_EINVAL),                                 # not a multiple of 32
     (dict(group=96), B.BASQ_EINVAL),                                  # does not divide K
-    (dict(group=128, Aq6=FAKE), B.BASQ_EINVAL),                       # the fp6 form is per-token only
+    (dict(K=1056, ldx=1056, rot=32, group=96, Aq6=FAKE), B.BASQ_EINVAL),   # fp6 form with groups: still K % 128 == 0
     (dict(clip_lo=0.0), B.BASQ_EINVAL),
     (dict(clip_hi=1.5), B.BASQ_EINVAL),
     (dict(clip_lo=float("nan")), B.BASQ_EINVAL),
@@ -153,11 +153,16 @@ def test_decode_layout_sizes_and_argument_checks(lib):
 
 
 def test_grouped_gemm_argument_checks(lib):
-    call = lambda M, K, G, gs=FAKE: lib.basq_w4a4_gemm_grouped(FAKE, FAKE, M, K, G, FAKE, 32, FAKE, FAKE, gs, None, FAKE, 32, None)
+    call = lambda M, K, G, gs=FAKE, a6=None, w6=None: lib.basq_w4a4_gemm_grouped(
+        FAKE, FAKE, M, K, G, FAKE, 32, FAKE, FAKE, gs, None, FAKE, 32, a6, w6, None)
     assert call(4, 256, 64) == B.BASQ_EUNSUPPORTED                     # only groups of 128
     assert call(4, 192, 128) == B.BASQ_EINVAL                          # K % 128
     assert call(4, 256, 128, None) == B.BASQ_EINVAL
     assert call(0, 256, 128) == 0                                      # no tokens: nothing launched
+    assert call(4, 256, 128, FAKE, FAKE, None) == B.BASQ_EINVAL        # fp6 operands: both or neither
+    assert call(4, 256, 128, FAKE, None, FAKE) == B.BASQ_EINVAL
+    assert call(4, 256, 128, FAKE, FAKE, ctypes.c_void_p(0x1008)) == B.BASQ_EINVAL
+    assert call(0, 256, 128, FAKE, FAKE, FAKE) == 0
     assert lib.basq_group_colsums(FAKE, 8, 192, 128, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_group_colsums(FAKE, 8, 256, 32, FAKE, None) == B.BASQ_EUNSUPPORTED
     assert lib.basq_group_colsums(None, 8, 256, 128, FAKE, None) == B.BASQ_EINVAL

@@ -372,7 +372,8 @@ def test_groupwise_ranges_generic_kernel(K, rot, group):
 # ---------------------------------------------------------------- group-wise ranges through the GEMM
 
 def run_grouped_layer(M, K, N, rot, *, seed=0, scale=False, odd_ldy=False):
-    """rotate+quant with group_size = 128, then basq_w4a4_gemm_grouped, against oracle.linear_grouped:
+    """rotate+quant with group_size = 128, then basq_w4a4_gemm_grouped (int8 path, then fp6 path: same bits), against
+    oracle.linear_grouped:
     (i) codes and group records bit-exact on the GPU's rotation; group column sums bit-exact;
     (ii) outputs: element by element within one bf16 step (2^-8 relative) plus 1e-5 of max|ref| of the oracle's
     output on the same codes (the kernel sums the groups in fp32, the oracle in fp64), and within 2e-2 of
@@ -404,10 +405,22 @@ def run_grouped_layer(M, K, N, rot, *, seed=0, scale=False, odd_ldy=False):
     ldy = N + 3 if odd_ldy else N
     Ybuf = torch.full((M, ldy), float("nan"), dtype=torch.bfloat16, device=dev)
     Y = Ybuf[:, :N]
-    B.basq_rotate_quant(X, rot, tb, ts, 0.9, 0.95, Aq, meta, rot_out, group_size=G)
+    A6 = B.alloc_fp6_buffer(M, K, dev).zero_()
+    A6b = torch.zeros_like(A6)
+    W6 = B.alloc_fp6_buffer(N, K, dev).zero_()
+    B.basq_rotate_quant(X, rot, tb, ts, 0.9, 0.95, Aq, meta, rot_out, group_size=G, Aq6=A6)
     B.basq_group_colsums(Wq, G, gsum)
     B.basq_w4a4_gemm_grouped(Aq, meta, G, Wq, w_scale, w_zero, gsum, out_bias, Y)
+    # the same product on the fp6 matrix-core path: bit-identical outputs
+    B.basq_pack_fp6(Aq, A6b)
+    B.basq_pack_fp6(Wq, W6)
+    Y6buf = torch.full((M, ldy), float("nan"), dtype=torch.bfloat16, device=dev)
+    B.basq_w4a4_gemm_grouped(Aq, meta, G, Wq, w_scale, w_zero, gsum, out_bias, Y6buf[:, :N], Aq6=A6, Wq6=W6)
     torch.cuda.synchronize()
+    assert torch.equal(A6, A6b), "fp6 copy written with group-wise ranges differs from the packed codes"
+    assert torch.equal(Y6buf[:, :N].view(torch.int16), Y.view(torch.int16)), "fp6 and int8 group-wise GEMMs differ"
+    if odd_ldy:
+        assert torch.isnan(Y6buf[:, N:]).all(), "fp6 path wrote past the row"
     np.testing.assert_array_equal(gsum.cpu().numpy(), oracle.group_colsums(wq, G), err_msg="group column sums")
     ref_i = oracle.linear_grouped(x, rot, b, sa, 0.9, 0.95, G, wq, c, r=rot_out.cpu().numpy())
     np.testing.assert_array_equal(oracle.unpack_codes(Aq.cpu().numpy()), ref_i.tq.codes, err_msg="codes")
