@@ -153,12 +153,14 @@ def main():
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
     B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
     use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > B.STREAM_MAX_TOKENS and group in (0, K)
+    g_fp6 = grouped and args.matrix_path == "fp6" and M > 0          # group-wise GEMM on the fp6 matrix-core path
+    want6 = use_fp6 or g_fp6
     w_gsum = None
     if grouped:
         w_gsum = torch.empty((K // 128, N), dtype=torch.int32, device=dev)
         B.basq_group_colsums(Wq, 128, w_gsum)
     Wq6 = None
-    if use_fp6:                                # offline: the weights once more in the fp6 operand form
+    if want6:                                # offline: the weights once more in the fp6 operand form
         Wq6 = B.alloc_fp6_buffer(N, K, dev)
         B.basq_pack_fp6(Wq, Wq6)
     # decode shapes stream the weights once per call: the streaming layout (offline repack), and as many
@@ -179,7 +181,7 @@ def main():
 
     # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
     rq_only = args.only == "rotate_quant"
-    per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2) + (M * K * 3 // 4 if use_fp6 else 0)
+    per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2) + (M * K * 3 // 4 if want6 else 0)
     nsets = args.sets if args.sets > 0 else max(2, min(32, -(-(640 << 20) // per_set)))
     X0 = lay.X.to(dev)
     sets = []
@@ -189,7 +191,7 @@ def main():
         if group not in (0, K):
             meta = torch.empty((M * (K // group), 4), dtype=torch.int32, device=dev)
         Y = None if rq_only else torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-        Aq6 = B.alloc_fp6_buffer(M, K, dev) if use_fp6 else None
+        Aq6 = B.alloc_fp6_buffer(M, K, dev) if want6 else None
         sets.append((Xi, Aq, meta, Y, Aq6))
     workspace = torch.empty(max(256, B.basq_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
@@ -203,7 +205,8 @@ def main():
     def gemm(i):
         _, Aq, meta, Y, Aq6 = sets[i % nsets]
         if grouped:
-            B.basq_w4a4_gemm_grouped(Aq, meta, 128, Wq, w_scale, w_zero, w_gsum, out_bias, Y, stream=stream)
+            B.basq_w4a4_gemm_grouped(Aq, meta, 128, Wq, w_scale, w_zero, w_gsum, out_bias, Y,
+                                     Aq6=Aq6 if g_fp6 else None, Wq6=Wq6 if g_fp6 else None, stream=stream)
             return
         B.basq_w4a4_gemm(Aq, meta, wsets[i % len(wsets)], w_scale, w_zero, w_sum, out_bias, Y, None, Aq6=Aq6, Wq6=Wq6,
                          w_layout=w_layout, N=N, stream=stream)
@@ -332,7 +335,7 @@ def main():
                 ceilings["hbm_read_GBps"] = views[0].numel() / (ms * 1e-3) / 1e9
             del rout
 
-    rq_bytes = algorithmic_bytes_rotate_quant(M, K, use_fp6, group)
+    rq_bytes = algorithmic_bytes_rotate_quant(M, K, want6, group)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N, use_fp6)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     if rq_only:
@@ -344,9 +347,9 @@ def main():
                 "algorithmic_bytes": gemm_bytes, "avg_kernel_ms": gemm_ms}
     else:
         ach = ops / (gemm_ms * 1e-3) / 1e12
-        peak = FP6_PEAK_TOPS if use_fp6 else INT8_PEAK_TOPS
+        peak = FP6_PEAK_TOPS if want6 else INT8_PEAK_TOPS
         tkey = "gemm_fp6" if use_fp6 else "gemm"
-        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else ("gemm_w4a4_grouped_kernel" if grouped else "gemm_w4a4_direct_kernel"),
+        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else (("gemm_w4a4_grouped_fp6_kernel" if g_fp6 else "gemm_w4a4_grouped_kernel") if grouped else "gemm_w4a4_direct_kernel"),
                 "bound": "mfma",
                 "achieved": ach, "peak": peak, "unit": "TOP/s", "frac": ach / peak,
                 "traffic": MEASURED_TRAFFIC.get((args.config, tkey)), "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
@@ -381,7 +384,7 @@ def main():
         "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
         "value": rq_gbs if rq_only else value, "unit": "GB/s" if rq_only else "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if use_fp6 and not rq_only
+        "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if want6 and not rq_only
                   else "int4 x int4 -> int32 (int8 MFMA)") + "; rotation and quantiser in f32; bf16 in/out",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": rot_size, "group_size": group if group else K,
@@ -390,7 +393,7 @@ def main():
                    "launch": "HIP graph replay of the K steps" if args.graph else "eager",
                    "step_launches": 1 if (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192)
                                           and rot_size == K) else 2,
-                   "matrix_path": "fp6" if use_fp6 else ("int4 weight streaming" if decode else "int8")},
+                   "matrix_path": "fp6" if want6 else ("int4 weight streaming" if decode else "int8")},
         "rotate_quant_GBps": rq_gbs,
         "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,

@@ -9,11 +9,11 @@
 // One LDS stage holds exactly one group (64 packed bytes per row), so a group's integer accumulator closes with
 // the stage: it is scaled into an fp32 accumulator (convert, two multiply-adds per element) and starts again
 // from zero.  On this chip fp32 vector multiply-adds do not run alongside MFMAs (a probe: 16 of them per
-// 64-cycle int8 MFMA halve the MFMA rate, 16 integer instructions cost nothing), so a group costs its MFMA time
-// plus its scaling time -- about 1000 + 800 cycles per wave on the int8 path, where the scaling would be three
-// times the MFMA time on the fp6 path.  Hence the int8 matrix cores, and wave tiles of 64 x 64 (an integer and
-// an fp32 accumulator set must fit the registers).  Running the two waves of a SIMD in opposite phases, or
-// interleaving the scaling of group g-1 with the MFMAs of group g, was measured and is no faster for that reason.
+// int8 MFMA halve the MFMA rate, 16 integer instructions cost nothing), so a group costs its MFMA time
+// plus its scaling time, and wave tiles are 64 x 64 (an integer and an fp32 accumulator set must fit the
+// registers).  Running the two waves of a SIMD in opposite phases, or interleaving the scaling of group g-1 with
+// the MFMAs of group g, was measured and is no faster for that reason.  This is the path for callers without the
+// fp6 operand forms; with them gemm_w4a4_grouped_fp6.hip computes the same bits in three quarters of the time.
 // Operands and the per-group constants (128 token records, 128 column sums) arrive by direct-to-LDS loads.
 #include "basq_internal.h"
 

@@ -191,7 +191,19 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
         for (int i = 0; i < G6G_TM; ++i)
 #pragma unroll
             for (int j = 0; j < G6G_TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[set][i], pb[set][j], from_zero ? zero : acc[i][j], 2, 2, 0, 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pb[set][j], pa[set][i], from_zero ? zero : acc[i][j], 2, 2, 0, 0, 0, 0);
+    };
+    // The weights are the first MFMA operand: accumulator register r of lane l belongs to token l % 32 of the row
+    // block and to output channel 8*(r/4) + 4*(l/32) + r%4 of the column block.  A lane then needs one token record
+    // per row block and group, and the 32 column sums come as eight 16-byte reads that are the same address for
+    // half a wave.  The column sums are kept in LDS as floats, already divided by 64: waves 0 and 1 convert the slot
+    // of group g+1 in place after the barrier of step g (64 values each); its readers come after the next barrier.
+    auto convert_colsums_load = [&](int g) -> int {
+        return *reinterpret_cast<const int*>(pring + (g % G6G_PSLOTS) * G6G_PSLOT_BYTES + 2048 + (swave * 64 + lane) * 4);
+    };
+    auto convert_colsums_store = [&](int g, int v) {
+        *reinterpret_cast<int*>(pring + (g % G6G_PSLOTS) * G6G_PSLOT_BYTES + 2048 + (swave * 64 + lane) * 4) =
+            __float_as_int(0.015625f * (float)v);
     };
 
     // ---- prologue: operands and constants of the first two groups.  A wave's loads complete in the order it issued
@@ -205,6 +217,8 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
     } else {
         g6g_wait_loads_and_barrier<0>();
     }
+    if (swave < 2) convert_colsums_store(0, convert_colsums_load(0));
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // LDS only: the second stage stays in flight
     read_frags(lds, 0, 0);
 
     // One group.  The last one is peeled off the loop so that the compiler's LDS waits count only the operands in
@@ -220,34 +234,47 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
         __builtin_amdgcn_sched_barrier(0);
         // every read of this stage has been issued; pass the barrier behind which the next stage and the next
         // group's constants are complete and visible: only the operand loads just issued may stay in flight
+        int raw_cs = 0;
         if (decltype(has_next)::value) {
             if (ahead) g6g_wait_loads_and_barrier<G6G_LOADS>(); else g6g_wait_loads_and_barrier<0>();
             // the constants slot refilled now was read at the end of step g-1, which every wave has left
             if (ahead) issue_constants(g + 2);
+            if (swave < 2) raw_cs = convert_colsums_load(g + 1);
             read_frags(lds + ((g + 1) % G6G_STAGES) * G6G_STAGE_BYTES, 0, 0);
+        } else {
+            // the last group's column sums were converted during the step before: make that visible
+            g6g_wait_loads_and_barrier<0>();
         }
+        // this group's constants, requested ahead of the MFMAs that hide their latency.  Read as integers: the
+        // compiler puts a wait for every outstanding direct-to-LDS load in front of a float-typed LDS read, which
+        // would drain the ring in every step.
+        const uint8_t* slot = pring + (g % G6G_PSLOTS) * G6G_PSLOT_BYTES;
+        v2i szb[G6G_TM];
+        v4i csb[G6G_TN][4];
+#pragma unroll
+        for (int i = 0; i < G6G_TM; ++i)
+            szb[i] = *reinterpret_cast<const v2i*>(slot + (wm * G6G_WM + i * 32 + col_in_tile) * 16);   // scale, lo
+#pragma unroll
+        for (int j = 0; j < G6G_TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                csb[j][q] = *reinterpret_cast<const v4i*>(slot + 2048 + (wn * G6G_WN + j * 32 + 8 * q + 4 * rgrp) * 4);
         __builtin_amdgcn_sched_barrier(0);
         compute(1, false);
         __builtin_amdgcn_sched_barrier(0);
+        if (decltype(has_next)::value) {
+            if (swave < 2) convert_colsums_store(g + 1, raw_cs);
+        }
         // ---- close the group: F' += s_mg * S_g + z_mg * (colsum_g / 64)
-        const uint8_t* slot = pring + (g % G6G_PSLOTS) * G6G_PSLOT_BYTES;
-        float cs[G6G_TN];
 #pragma unroll
-        for (int j = 0; j < G6G_TN; ++j)
-            cs[j] = 0.015625f * (float)*reinterpret_cast<const int*>(slot + 2048 + (wn * G6G_WN + j * 32 + col_in_tile) * 4);
+        for (int i = 0; i < G6G_TM; ++i) {
+            const float sc = __int_as_float(szb[i][0]), lo = __int_as_float(szb[i][1]);
 #pragma unroll
-        for (int i = 0; i < G6G_TM; ++i)
+            for (int j = 0; j < G6G_TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
-                // read as integers: the compiler puts a wait for every outstanding direct-to-LDS load in front of a
-                // float-typed LDS read, which would drain the ring in every step
-                const v2i szb = *reinterpret_cast<const v2i*>(slot + (wm * G6G_WM + i * 32 + rloc) * 16);   // scale, lo
-                const float sc = __int_as_float(szb[0]), lo = __int_as_float(szb[1]);
-#pragma unroll
-                for (int j = 0; j < G6G_TN; ++j)
-                    facc[i][j][r] = fmaf(sc, acc[i][j][r], fmaf(lo, cs[j], facc[i][j][r]));
-            }
+                for (int r = 0; r < 16; ++r)
+                    facc[i][j][r] = fmaf(sc, acc[i][j][r], fmaf(lo, __int_as_float(csb[j][r >> 2][r & 3]), facc[i][j][r]));
+        }
     };
     int g = 0;
     for (; g + 1 < ngroups; ++g) k_step(g, std::true_type{});
@@ -276,9 +303,6 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
     }
     __syncthreads();
 
-    float4 cp[G6G_TN];
-#pragma unroll
-    for (int j = 0; j < G6G_TN; ++j) cp[j] = lcol[wn * G6G_WN + j * 32 + col_in_tile];
     const bool vec_ok = (a.ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(a.Y) & 15) == 0;
     constexpr int PITCH = G6G_WN * 2 + 16;                       // bytes
     constexpr int CH_PER_ROW = G6G_WN / 8;                       // 16-byte pieces per row
@@ -287,18 +311,19 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
     static_assert(4096 + G6G_WAVES * 32 * PITCH <= G6G_STAGES * G6G_STAGE_BYTES, "epilogue staging does not fit");
 #pragma unroll
     for (int i = 0; i < G6G_TM; ++i) {
+        const float R = lrow[wm * G6G_WM + i * 32 + col_in_tile].x;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int rloc = 8 * (r >> 2) + 4 * rgrp + (r & 3);
-            const float R = lrow[wm * G6G_WM + i * 32 + rloc].x;
+        for (int j = 0; j < G6G_TN; ++j) {
 #pragma unroll
-            for (int j = 0; j < G6G_TN; ++j) {
-                const float y = fmaf(cp[j].x, 64.0f * facc[i][j][r], fmaf(-cp[j].y, R, cp[j].z));
+            for (int r = 0; r < 16; ++r) {
+                const int cloc = j * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
+                const float4 cp = lcol[wn * G6G_WN + cloc];
+                const float y = fmaf(cp.x, 64.0f * facc[i][j][r], fmaf(-cp.y, R, cp.z));
                 if (vec_ok) {
-                    *reinterpret_cast<uint16_t*>(patch + rloc * PITCH + (j * 32 + col_in_tile) * 2) = f32_to_bf16(y);
+                    *reinterpret_cast<uint16_t*>(patch + col_in_tile * PITCH + cloc * 2) = f32_to_bf16(y);
                 } else {
-                    const int64_t m = m0 + wm * G6G_WM + i * 32 + rloc;
-                    const int n = n0 + wn * G6G_WN + j * 32 + col_in_tile;
+                    const int64_t m = m0 + wm * G6G_WM + i * 32 + col_in_tile;
+                    const int n = n0 + wn * G6G_WN + cloc;
                     if (m < a.M && n < a.N) a.Y[m * a.ldy + n] = f32_to_bf16(y);
                 }
             }
