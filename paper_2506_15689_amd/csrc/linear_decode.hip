@@ -77,7 +77,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
         const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, false, false>(
             raw, bop, tr + wave * P2_LDS_WORDS, reinterpret_cast<const float4*>(lbias_s), q.act_scale, nullptr, norm,
             q.clip_lo, q.clip_hi, lane, pl.wbase, pl.rbase, []() {},
-            [&](int hf, int b, const uint32_t (&words)[4], const uint32_t (&)[4], const uint32_t (&)[4]) {
+            [&](int hf, int b, const uint32_t (&words)[4], const v16f&, const v16f&) {
                 *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 2048 * hf + 1024 * b + 16 * lane) =
                     make_uint4(words[0], words[1], words[2], words[3]);
             },

@@ -129,9 +129,10 @@ struct P2Meta { float scale, lo; int rowsum; };
 
 // raw: the token as loaded with P2Lane::chunk (raw[c] = 16 bytes at channel 512*c + 8*chunk).  wl: this wave's
 // P2_LDS_WORDS floats.  lbias: the staged bias.  rot_row: where the fp32 rotation of this token goes (ROT_OUT).
-// after_mfma(): called once raw[] is dead.  sink(hf, b, words, evs, ods): the 32 codes of channels
-// 4096*hf + 2048*b + 32*lane .. +31 -- words: packed two per byte (16 bytes), evs/ods: byte j of evs[w] = code
-// 8w + 2j, of ods[w] = code 8w + 2j + 1.
+// after_mfma(): called once raw[] is dead.  sink(hf, b, words, te, to): the 32 codes of channels
+// 4096*hf + 2048*b + 32*lane .. +31 -- words: packed two per byte (16 bytes); te[i] / to[i]: the clamped but not
+// yet rounded value fma(v, inv, nlo) in [0, 15] of channel 2i / 2i + 1, whose rounding to nearest-even is the code
+// (for callers that want the codes in another number format: a conversion that rounds the same way gives them).
 // NC: 16-byte loads per lane per token (K = 512 * NC).  Without FOLD_NORM one fp32 multiply by `norm` follows
 // the butterflies.
 // GROUPED: one range per 128 consecutive channels instead of one per token (four neighbouring lanes own a group);
@@ -287,7 +288,8 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
                 range_constants(vmin, vmax);
                 sum = 0;
             }
-            uint32_t words[4], evs[4], ods[4];
+            uint32_t words[4];
+            v16f te, to;
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 uint32_t ev = 0, od = 0;
@@ -297,13 +299,14 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
                     const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
                     ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
                     od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
+                    te[4 * w + j] = t0;
+                    to[4 * w + j] = t1;
                 }
                 sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
                 sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
                 words[w] = ev | (od << 4);
-                evs[w] = ev; ods[w] = od;
             }
-            sink(hf, b, words, evs, ods);
+            sink(hf, b, words, te, to);
             if (GROUPED) {
                 sum += dpp_i<DPP_QUAD_XOR1>(sum);
                 sum += dpp_i<DPP_QUAD_XOR2>(sum);

@@ -70,21 +70,15 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
             lane, pl.wbase, pl.rbase,
             // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
             [&]() { if (PREFETCH && mnext < a.M) load_token(mnext); },
-            [&](int hf, int b, const uint32_t (&words)[4], const uint32_t (&evs)[4], const uint32_t (&ods)[4]) {
+            [&](int hf, int b, const uint32_t (&words)[4], const v16f& te, const v16f& to) {
                 uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
                 nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
                 if (a.Aq6) {
-                    // the same 32 codes as e2m3 numbers q/8: the packed conversion divides by its scale
-                    // operand and interleaves its two sources (even and odd codes)
-                    v16f qe, qo;
-#pragma unroll
-                    for (int w = 0; w < 4; ++w)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            qe[4 * w + j] = (float)((evs[w] >> (8 * j)) & 0xFFu);
-                            qo[4 * w + j] = (float)((ods[w] >> (8 * j)) & 0xFFu);
-                        }
-                    const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 8.0f);
+                    // The same 32 codes as e2m3 numbers q/8, straight from the clamped values t in [0, 15]: the
+                    // packed conversion divides by its scale operand, rounds to nearest-even -- on the e2m3 grid
+                    // below 2 that is t/8 -> rint(t)/8, ties to the even code as in the integer conversion -- and
+                    // interleaves its two sources (even and odd channels).
+                    const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(te, to, 8.0f);
                     // group 128*hf + 64*b + lane of the token: chunk (group / 4), position (group % 4)
                     const int g = 128 * hf + 64 * b + lane, f = g & 3, r = (int)(m & 31);
                     uint8_t* blk = a.Aq6 + ((int64_t)(g >> 2) * rb6 + (m >> 5)) * 3072;

@@ -183,6 +183,38 @@ def test_degenerate_tokens_match_oracle():
     assert mh[1, 0].view(np.float32) == 1.0 and (codes[1] == 0).all()
 
 
+@pytest.mark.parametrize("K", [512, 4096, 8192, 14336])
+def test_ties_round_to_even_in_both_code_forms(K):
+    """Values exactly half-way between two codes: an all-zero input rotates to zero, so v = -b^c, and with the range
+    [0, 15] and clip ratios of 1 the quantiser's step is exactly 1 and t = v.  Every k + 1/2 must become the even
+    neighbour in the packed INT4 codes (integer conversion) and in the fp6 copy, which the K = 4096 / 8192 kernel
+    makes with a floating-point conversion of its own (K = 512 and 14336: the other kernels, for comparison)."""
+    dev = "cuda"
+    M = 5
+    v = (np.arange(K) % 15).astype(np.float32) + 0.5
+    v[0], v[1] = 0.0, 15.0
+    v[2::7] = (np.arange(len(v[2::7])) % 16).astype(np.float32)        # some exact codes in between
+    X = torch.zeros((M, K), dtype=torch.bfloat16, device=dev)
+    X[3, 5] = float("nan")                   # rotates to NaN everywhere: every code is 0, in both forms
+    X[4, 9] = float("inf")                   # rotates to +-inf: codes 15 and 0, the same in both forms
+    bias = torch.from_numpy(-v).to(dev)
+    Aq, meta = B.alloc_activation_buffers(M, K, dev)
+    A6 = B.alloc_fp6_buffer(M, K, dev).zero_()
+    A6b = torch.zeros_like(A6)
+    B.basq_rotate_quant(X, K, bias, None, 1.0, 1.0, Aq, meta, Aq6=A6)
+    B.basq_pack_fp6(Aq, A6b)
+    torch.cuda.synchronize()
+    tq = oracle.quantize_tokens(np.zeros((M, K), dtype=np.float32), bias.cpu().numpy(), None, 1.0, 1.0)
+    expect = np.rint(v).astype(tq.codes.dtype)                           # numpy rounds half to even
+    np.testing.assert_array_equal(tq.codes, np.broadcast_to(expect, (M, K)))
+    codes = oracle.unpack_codes(Aq.cpu().numpy())
+    np.testing.assert_array_equal(codes[:3], tq.codes[:3])
+    assert (codes[3] == 0).all() and set(np.unique(codes[4])) <= {0, 15}
+    mh = meta.cpu().numpy()
+    assert (mh[:3, 0].copy().view(np.float32) == 1.0).all() and (mh[:3, 1].copy().view(np.float32) == 0.0).all()
+    assert torch.equal(A6, A6b), "the fp6 copy written by the quantiser differs from the packed codes"
+
+
 def test_strided_input_and_output():
     dev = "cuda"
     lay = si.make_tiny(50, 256, 48, seed=31)
