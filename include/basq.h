@@ -88,7 +88,9 @@ const char* basq_last_error(void);
  *   meta       out, [M, K/group_size] records, token-major (group_size 0 counts as K)
  *   rot_out    out, optional debug dump of r, fp32 [M, K]; NULL to skip
  *   Aq6        out, optional (NULL to skip): the same codes in the fp6 operand form described at
- *              basq_pack_fp6 (basq_fp6_bytes(M, K) bytes), 16-byte aligned; needs K % 128 == 0
+ *              basq_pack_fp6 (basq_fp6_bytes(M, K) bytes), 16-byte aligned; needs K % 128 == 0.  With per-token
+ *              ranges and rot_size == K in {4096, 8192, 14336} the quantiser writes it itself; otherwise (other
+ *              sizes, group-wise ranges) a packing pass follows on the same stream.
  * M == 0 is valid and does nothing.
  */
 int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
