@@ -42,6 +42,7 @@ import pytest
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("args", [["--config", "C1"], ["--config", "C3_M4"], ["--config", "C1", "--group-size", "128"],
+                                  ["--config", "C1", "--group-size", "128", "--matrix-path", "int8"],
                                   ["--config", "C1", "--only", "rotate_quant", "--rot-size", "128", "--group-size", "128"],
                                   ["--config", "C3_M1", "--graph"]])
 def test_bench_prints_one_json_line_with_the_contract_fields(args):
