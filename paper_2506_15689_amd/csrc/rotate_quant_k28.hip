@@ -289,6 +289,7 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         uint32_t words[4][4];                              // [jb][r]: 16 bytes of codes per jb
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) {
+            v16f qe, qo;                                   // the clamped values before rounding: low / high nibbles
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 uint32_t ev = 0, od = 0;
@@ -298,6 +299,8 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                     const float t1 = __builtin_amdgcn_fmed3f(fmaf(d[jb][2 * p + 1][r], inv, nlo), 0.0f, 15.0f);
                     ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, p, ev);
                     od = __builtin_amdgcn_cvt_pk_u8_f32(t1, p, od);
+                    qe[4 * r + p] = t0;
+                    qo[4 * r + p] = t1;
                 }
                 if (row_valid) {
                     sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
@@ -306,17 +309,10 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
                 words[jb][r] = ev | (od << 4);
             }
             if (a.Aq6 && row_valid && tok_valid) {
-                // The 32 codes of group jb once more, as e2m3 numbers q/8 (the packed conversion divides by
-                // its scale operand and interleaves even and odd codes).  A lane's 128 channels are one
-                // 128-code chunk of the fp6 layout: chunk 4*i' + g, group jb.
-                v16f qe, qo;
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        qe[4 * r + p] = (float)((words[jb][r] >> (8 * p)) & 0xFu);
-                        qo[4 * r + p] = (float)((words[jb][r] >> (8 * p + 4)) & 0xFu);
-                    }
+                // The 32 codes of group jb once more, as e2m3 numbers q/8, straight from the clamped values: the
+                // packed conversion divides by its scale operand, rounds to nearest-even (on the e2m3 grid below 2
+                // that is t/8 -> rint(t)/8, ties as in the integer conversion) and interleaves its two sources.
+                // A lane's 128 channels are one 128-code chunk of the fp6 layout: chunk 4*i' + g, group jb.
                 const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(qe, qo, 8.0f);
                 const int rr = (int)(m & 31);
                 uint8_t* blk = a.Aq6 + ((int64_t)(4 * ip + g) * rb6 + (m >> 5)) * 3072;
