@@ -7,32 +7,33 @@ namespace basq {
 
 namespace {
 
-#ifndef P2_WAVES_CFG
-#define P2_WAVES_CFG 4
-#endif
-constexpr int P2_WAVES = P2_WAVES_CFG;      // wavefronts per workgroup
-constexpr int P2_THREADS = P2_WAVES * 64;
-#ifndef P2_OCC_4096
-#define P2_OCC_4096 3
-#endif
-#ifndef P2_PREFETCH
-#define P2_PREFETCH 1
-#endif
-
 // NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
 // sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
 // GROUPED: one range and one record per 128 channels (group_size = 128) instead of per token.
-template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED>
-__global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
+// WAVES: wavefronts (= tokens in flight) per workgroup, 4 or 8.  Eight halve the number of workgroups that each
+// stage the channel bias, which shows at a few thousand tokens; K = 4096 then runs two waves per SIMD instead of
+// three, which costs 3 % at very large M.
+// STAGE_TAILS (WAVES = 8, with the fp6 copy): the 8-byte tail pieces of the fp6 form are collected in LDS and
+// leave as the 64 contiguous bytes that the workgroup's eight consecutive tokens own in every tail row.  An 8-byte
+// store is one request to the L2 however it is aligned, and with them a token makes 385 write requests instead
+// of 65; staged it is 161 (measured: 65536 tokens of K = 4096 in 170 us against 222 us).  The two barriers per
+// round cost more than that saves below about 32768 tokens.
+template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED, int WAVES, bool STAGE_TAILS>
+__global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
     constexpr int K = 512 * NC;
-    constexpr bool PREFETCH = (NC == 8) && P2_PREFETCH;
-    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves)
+    constexpr int THREADS = WAVES * 64;
+    constexpr bool PREFETCH = (NC == 8);
+    static_assert(WAVES == 4 || WAVES == 8, "workgroups of four or eight wavefronts");
+    static_assert(!STAGE_TAILS || (WAVES == 8 && !GROUPED), "the staged tails are those of eight consecutive tokens");
+    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves), then the tail stage
     constexpr int BIAS_WORDS = HAS_BIAS ? K : 0;
-    __shared__ __attribute__((aligned(16))) float lds[P2_WAVES * P2_LDS_WORDS + BIAS_WORDS];
+    constexpr int TS_BYTES = STAGE_TAILS ? (K / 32) * WAVES * 8 : 0;      // per 32-channel group: 8 bytes per token
+    __shared__ __attribute__((aligned(16))) float lds[WAVES * P2_LDS_WORDS + BIAS_WORDS + TS_BYTES / 4];
+    uint8_t* const tstage = reinterpret_cast<uint8_t*>(lds + WAVES * P2_LDS_WORDS + BIAS_WORDS);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* wl = lds + wave * P2_LDS_WORDS;
-    const float4* lbias = reinterpret_cast<const float4*>(lds + P2_WAVES * P2_LDS_WORDS);
+    const float4* lbias = reinterpret_cast<const float4*>(lds + WAVES * P2_LDS_WORDS);
     v8bf bop[2];
     p2_make_bop<NC, FOLD_NORM>(lane, bop);
     const P2Lane pl = p2_lane(lane);
@@ -42,8 +43,8 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     // 16-byte pieces merge into whole lines before they are written back.
     int vblock = blockIdx.x;
     if (a.Aq6 && (gridDim.x & 63) == 0) vblock = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int wave_id = vblock * P2_WAVES + wave;
-    const int wave_stride = gridDim.x * P2_WAVES;
+    const int wave_id = vblock * WAVES + wave;
+    const int wave_stride = gridDim.x * WAVES;
     const int64_t rb6 = (a.M + 31) >> 5;                       // 32-row blocks per chunk of the fp6 output
 
     uint4 raw[NC];
@@ -58,11 +59,14 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
     int64_t m = wave_id;
     if (PREFETCH && m < a.M) load_token(m);
     if (HAS_BIAS) {
-        p2_stage_bias<K>(lds + P2_WAVES * P2_LDS_WORDS, a.bias, threadIdx.x, P2_THREADS);
+        p2_stage_bias<K>(lds + WAVES * P2_LDS_WORDS, a.bias, threadIdx.x, THREADS);
         __syncthreads();
     }
 
-    for (; m < a.M; m += wave_stride) {
+    // One round per iteration: the workgroup's waves take WAVES consecutive tokens (a whole number of rounds for
+    // every wave, since the staged variant meets at barriers).
+    for (int64_t mbase = (int64_t)vblock * WAVES; mbase < a.M; mbase += wave_stride, m += wave_stride) {
+      if (m < a.M) {
         if (!PREFETCH) load_token(m);
         const int64_t mnext = m + wave_stride;
         const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, ROT_OUT, GROUPED>(
@@ -84,7 +88,11 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
                     uint8_t* blk = a.Aq6 + ((int64_t)(g >> 2) * rb6 + (m >> 5)) * 3072;
                     *reinterpret_cast<uint4*>(blk + 64 * r + 16 * (f ^ ((r >> 2) & 3))) =
                         make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
-                    *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
+                    if (STAGE_TAILS)     // slot of this wave's token in the group's 64 bytes, swizzled against bank conflicts
+                        *reinterpret_cast<uint2*>(tstage + g * (WAVES * 8) + 8 * (wave ^ ((g >> 1) & 7))) =
+                            make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
+                    else
+                        *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
                 }
             },
             [&](int hf, int b, float gs, float glo, int gsum) {
@@ -99,30 +107,58 @@ __global__ __launch_bounds__(P2_THREADS, (NC == 8 ? P2_OCC_4096 : 2)) void rotat
             mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum; mt.reserved = 0;
             a.meta[m] = mt;
         }
+      }
+      if (STAGE_TAILS && a.Aq6) {
+        // the tails of tokens mbase .. mbase + 7 (one 32-row block: mbase is a multiple of 8): 16 bytes per thread,
+        // four neighbouring threads write the 64 bytes of one group
+        __syncthreads();
+        constexpr int PIECES = TS_BYTES / 16;
+        for (int p = threadIdx.x; p < PIECES; p += THREADS) {
+            const int g = p / (WAVES / 2), q = p % (WAVES / 2);          // tokens mbase + 2q, + 2q + 1 of group g
+            const int64_t mt = mbase + 2 * q;
+            if (mt < a.M) {
+                const int sw = (g >> 1) & 7;
+                const uint2 v0 = *reinterpret_cast<const uint2*>(tstage + g * (WAVES * 8) + 8 * ((2 * q) ^ sw));
+                const uint2 v1 = *reinterpret_cast<const uint2*>(tstage + g * (WAVES * 8) + 8 * ((2 * q + 1) ^ sw));
+                uint8_t* dst = a.Aq6 + ((int64_t)(g >> 2) * rb6 + (mbase >> 5)) * 3072 + 2048 + 256 * (g & 3) + 8 * (int)(mt & 31);
+                if (mt + 1 < a.M) *reinterpret_cast<uint4*>(dst) = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                else *reinterpret_cast<uint2*>(dst) = v0;
+            }
+        }
+        __syncthreads();                 // the next round's tails go to the same stage
+      }
     }
 }
 
-template <int NC, bool FOLD, bool HB, bool HS>
-int launch_flags(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm) {
-    const bool grouped = a.group != a.K;
-    if (a.rot_out && grouped)
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
-    else if (grouped)
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false, true>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
-    else if (a.rot_out)
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, true, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
-    else
-        hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, false, false>), dim3(blocks), dim3(P2_THREADS), 0, s, a, norm);
+template <int NC, bool FOLD, bool HB, bool HS, bool RO, bool GR, int WAVES, bool STAGE>
+int launch_one(const RotateQuantArgs& a, hipStream_t s, float norm) {
+    const int64_t want = (a.M + WAVES - 1) / WAVES;
+    const int64_t resident = 256 * (NC == 8 && WAVES == 4 ? 3 : 2) * 4 / WAVES;     // workgroups the chip holds at once
+    const unsigned blocks = (unsigned)(want < resident ? want : resident);        // waves loop over tokens
+    hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, RO, GR, WAVES, STAGE>), dim3(blocks), dim3(WAVES * 64), 0, s, a, norm);
     return check_hip(hipGetLastError(), "rotate_quant (pow2) launch");
 }
 
+template <int NC, bool FOLD, bool HB, bool HS>
+int launch_flags(const RotateQuantArgs& a, hipStream_t s, float norm) {
+    const bool grouped = a.group != a.K;
+    if (a.rot_out && grouped) return launch_one<NC, FOLD, HB, HS, true, true, 4, false>(a, s, norm);
+    if (grouped) return launch_one<NC, FOLD, HB, HS, false, true, 4, false>(a, s, norm);
+    if (a.rot_out) return launch_one<NC, FOLD, HB, HS, true, false, 4, false>(a, s, norm);
+    // measured: the tail stage pays from about 32768 tokens on; without it eight waves per workgroup help K = 4096
+    // up to there (10 % at 2048 .. 16384 tokens) and K = 8192 up to about 4096 tokens (4 %), and are neutral beyond
+    if (a.Aq6 && a.M >= 32768) return launch_one<NC, FOLD, HB, HS, false, false, 8, true>(a, s, norm);
+    if ((NC == 8 && a.M < 32768) || (NC == 16 && a.M <= 4096)) return launch_one<NC, FOLD, HB, HS, false, false, 8, false>(a, s, norm);
+    return launch_one<NC, FOLD, HB, HS, false, false, 4, false>(a, s, norm);
+}
+
 template <int NC, bool FOLD>
-int launch_nc(const RotateQuantArgs& a, hipStream_t s, unsigned blocks, float norm) {
+int launch_nc(const RotateQuantArgs& a, hipStream_t s, float norm) {
     const bool hb = a.bias != nullptr, hs = a.act_scale != nullptr;
-    if (hb && hs) return launch_flags<NC, FOLD, true, true>(a, s, blocks, norm);
-    if (hb) return launch_flags<NC, FOLD, true, false>(a, s, blocks, norm);
-    if (hs) return launch_flags<NC, FOLD, false, true>(a, s, blocks, norm);
-    return launch_flags<NC, FOLD, false, false>(a, s, blocks, norm);
+    if (hb && hs) return launch_flags<NC, FOLD, true, true>(a, s, norm);
+    if (hb) return launch_flags<NC, FOLD, true, false>(a, s, norm);
+    if (hs) return launch_flags<NC, FOLD, false, true>(a, s, norm);
+    return launch_flags<NC, FOLD, false, false>(a, s, norm);
 }
 
 }  // namespace
@@ -134,12 +170,9 @@ bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
 }
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {
-    const int64_t want = (a.M + P2_WAVES - 1) / P2_WAVES;
-    const int64_t resident = 256 * (a.K == 4096 ? P2_OCC_4096 : 2) * 4 / P2_WAVES;  // workgroups the chip holds at once
-    const unsigned blocks = (unsigned)(want < resident ? want : resident);   // waves loop over tokens
     const float norm = (float)(1.0 / sqrt((double)a.K));
-    if (a.K == 4096) return launch_nc<8, true>(a, s, blocks, norm);
-    return launch_nc<16, false>(a, s, blocks, norm);
+    if (a.K == 4096) return launch_nc<8, true>(a, s, norm);
+    return launch_nc<16, false>(a, s, norm);
 }
 
 }  // namespace basq

@@ -215,6 +215,34 @@ def test_ties_round_to_even_in_both_code_forms(K):
     assert torch.equal(A6, A6b), "the fp6 copy written by the quantiser differs from the packed codes"
 
 
+@pytest.mark.parametrize("K", [4096, 8192])
+def test_many_tokens_take_the_staged_fp6_tails(K):
+    """From 32768 tokens on, the K = 4096 / 8192 kernel writes the 8-byte tail pieces of the fp6 copy through an LDS
+    stage shared by the eight tokens of a workgroup.  Same bits as the plain path: codes and records of the first and
+    last thousand tokens equal those of separate short calls (which the other tests pin to the oracle), and the fp6 copy
+    equals the packed codes everywhere; 13 tokens past a multiple of 8 leave a ragged, odd last round, and rows past M
+    in the last block stay untouched."""
+    dev = "cuda"
+    M = 32768 + 13
+    gen = torch.Generator(device=dev).manual_seed(K)
+    X = (torch.randn((M, K), generator=gen, device=dev) * 1.5).to(torch.bfloat16)
+    X[:, 7] *= 20.0                                                        # an outlier channel
+    bias = torch.randn(K, generator=gen, device=dev) * 0.1
+    Aq, meta = B.alloc_activation_buffers(M, K, dev)
+    A6 = B.alloc_fp6_buffer(M, K, dev).zero_()
+    A6b = torch.zeros_like(A6)
+    B.basq_rotate_quant(X, K, bias, None, 0.9, 0.95, Aq, meta, Aq6=A6)
+    B.basq_pack_fp6(Aq, A6b)
+    torch.cuda.synchronize()
+    assert torch.equal(A6, A6b), "the staged fp6 copy differs from the packed codes"
+    for lo, hi in ((0, 1000), (M - 1000, M)):
+        Aq_s, meta_s = B.alloc_activation_buffers(hi - lo, K, dev)
+        B.basq_rotate_quant(X[lo:hi], K, bias, None, 0.9, 0.95, Aq_s, meta_s)
+        torch.cuda.synchronize()
+        assert torch.equal(Aq[lo:hi], Aq_s) and torch.equal(meta[lo:hi], meta_s)
+    assert int(meta[:, 2].min()) >= 0 and int(meta[:, 2].max()) <= 15 * K
+
+
 def test_strided_input_and_output():
     dev = "cuda"
     lay = si.make_tiny(50, 256, 48, seed=31)
