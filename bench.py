@@ -33,9 +33,9 @@ FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
 # HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
 # under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
 MEASURED_TRAFFIC = {
-    ("C2", "rotate_quant"): 27568891, ("C2", "gemm"): 169999751, ("C2", "gemm_fp6"): 176946203,
-    ("C4", "rotate_quant"): 108649851, ("C4", "gemm"): 176765487, ("C4", "gemm_fp6"): 260375205,
-    ("C5", "rotate_quant"): 109642653, ("C5", "gemm"): 945049926, ("C5", "gemm_fp6"): 1294326691,
+    ("C2", "rotate_quant"): 27564191, ("C2", "gemm"): 170037084, ("C2", "gemm_fp6"): 176944755,
+    ("C4", "rotate_quant"): 110548863, ("C4", "gemm"): 176694503, ("C4", "gemm_fp6"): 260240288,
+    ("C5", "rotate_quant"): 109842228, ("C5", "gemm"): 945431192, ("C5", "gemm_fp6"): 1294320431,
     ("C3_M16", "rotate_quant"): 301233, ("C3_M16", "gemm"): 8985923,
     ("C3_M1", "rotate_quant"): 44642, ("C3_M1", "gemm"): 8616106,
 }
