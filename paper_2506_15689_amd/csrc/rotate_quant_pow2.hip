@@ -145,10 +145,12 @@ int launch_flags(const RotateQuantArgs& a, hipStream_t s, float norm) {
     if (a.rot_out && grouped) return launch_one<NC, FOLD, HB, HS, true, true, 4, false>(a, s, norm);
     if (grouped) return launch_one<NC, FOLD, HB, HS, false, true, 4, false>(a, s, norm);
     if (a.rot_out) return launch_one<NC, FOLD, HB, HS, true, false, 4, false>(a, s, norm);
-    // measured: the tail stage pays from about 32768 tokens on; without it eight waves per workgroup help K = 4096
-    // up to there (10 % at 2048 .. 16384 tokens) and K = 8192 up to about 4096 tokens (4 %), and are neutral beyond
+    // measured: the tail stage pays from about 32768 tokens on.  Without it, eight waves per workgroup help from 2048
+    // tokens (fewer workgroups stage the bias; below that, four-wave workgroups spread the tokens over more compute
+    // units, one wave per SIMD, which is worth 1-2 us) up to 32768 tokens for K = 4096 (10 % at 2048 .. 16384) and up
+    // to 4096 for K = 8192 (4-10 %), and are neutral or slightly worse beyond.
     if (a.Aq6 && a.M >= 32768) return launch_one<NC, FOLD, HB, HS, false, false, 8, true>(a, s, norm);
-    if ((NC == 8 && a.M < 32768) || (NC == 16 && a.M <= 4096)) return launch_one<NC, FOLD, HB, HS, false, false, 8, false>(a, s, norm);
+    if (a.M >= 2048 && ((NC == 8 && a.M < 32768) || (NC == 16 && a.M <= 4096))) return launch_one<NC, FOLD, HB, HS, false, false, 8, false>(a, s, norm);
     return launch_one<NC, FOLD, HB, HS, false, false, 4, false>(a, s, norm);
 }
 
