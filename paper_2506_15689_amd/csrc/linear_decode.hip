@@ -75,158 +75,33 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
 #pragma unroll
         for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
     };
-    // Pair mode: with one or two tokens of K = 4096, two waves share a token.  Wave `half` takes chunks
-    // 4*half .. 4*half+3 through the MFMA and the register stages; the last chunk stage (e11) pairs chunk c of one
-    // wave with chunk c of the other, so the two exchange their 32 values per lane through LDS and each keeps one
-    // output of every butterfly; after it a wave owns one 2048-channel half (b = half) for the transpose, the
-    // remaining stages and the quantiser, and only the token's range and row sum are combined across the two.
-    // Every value is produced by the same operations in the same order as in the one-wave routine: same bits.
+    // Pair mode: with one or two tokens of K = 4096, two waves share a token (p2_token_pair: same bits).
     const bool pair_mode = CAN_PAIR && M <= 2;                          // uniform over the grid
     if (pair_mode) {
         if (tid < LD_MAX_TOKENS) lsum_hi[tid] = 0;
         const int t = wave >> 1, half = wave & 1;
         const bool active = t < M;
-        float d[4][2][4];
+        uint4 raw4[4] = {};
         if (active) {
             const uint16_t* x = q.X + t * q.ldx + 8 * pl.chunk + 2048 * half;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = nt_load16(x + 512 * j);
+            for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
         }
-        if (HAS_BIAS) p2_stage_bias<K>(lbias_s, q.bias, tid, LD_THREADS);
-        if (active) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const v8bf aop = __builtin_bit_cast(v8bf, raw[j]);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    v4f acc = {0.f, 0.f, 0.f, 0.f};
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[h], acc, 0, 0, 0);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) d[j][h][r] = acc[r];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    BFLY(d[j][h][0], d[j][h][1]);
-                    BFLY(d[j][h][2], d[j][h][3]);
-                    BFLY(d[j][h][0], d[j][h][2]);
-                    BFLY(d[j][h][1], d[j][h][3]);
-                }
-#pragma unroll
-            for (int sft = 1; sft < 4; sft <<= 1)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if ((j & sft) == 0)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) BFLY(d[j][h][r], d[j + sft][h][r]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    xch[(wave * 8 + 2 * j + h) * 64 + lane] = make_float4(d[j][h][0], d[j][h][1], d[j][h][2], d[j][h][3]);
-        }
-        __syncthreads();
-        float p[32];
-        float mn = INFINITY, mx = -INFINITY;
-        if (active) {
-            // stage e11: chunk c of the lower wave with chunk c + 4 of the upper one
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const float4 o = xch[((wave ^ 1) * 8 + 2 * j + h) * 64 + lane];
-                    const float ov[4] = {o.x, o.y, o.z, o.w};
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) d[j][h][r] = half == 0 ? d[j][h][r] + ov[r] : ov[r] - d[j][h][r];
-                }
-            // transpose of this wave's 2048 channels, as in the one-wave routine
-            float* wl = tr + wave * P2_LDS_WORDS;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int c01 = 0; c01 < 4; ++c01) {
-                    const int r0 = r & 1, r1 = r >> 1;
-                    const int addr = (pl.wbase ^ ((r0 << 1) | (r1 << 2))) | (r0 << 5) | (r1 << 6) | (c01 << 9);
-                    *reinterpret_cast<float2*>(wl + addr) = make_float2(d[c01][0][r], d[c01][1][r]);
-                }
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int qq = 0; qq < 16; ++qq) {
-                const int e1 = qq & 1, e2 = (qq >> 1) & 1, e3 = (qq >> 2) & 1, e4 = qq >> 3;
-                const int addr = (pl.rbase ^ ((e1 << 1) | (e2 << 2))) | (e3 << 7) | (e4 << 8);
-                const float2 v = *reinterpret_cast<const float2*>(wl + addr);
-                const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
-                p[idx] = v.x;
-                p[idx | 1] = v.y;
-            }
-#pragma unroll
-            for (int i = 0; i < 32; ++i) if ((i & 8) == 0) BFLY(p[i], p[i | 8]);
-#pragma unroll
-            for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[i], p[i | 16]);
-            const int e0 = 2048 * half + 32 * lane;
-            const float4* lbias = reinterpret_cast<const float4*>(lbias_s);
-#pragma unroll
-            for (int i4 = 0; i4 < 8; ++i4) {
-                float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
-                if (HAS_BIAS) bb = lbias[(half * 8 + i4) * 64 + lane];
-                if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(q.act_scale + e0 + 4 * i4);
-                const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
-                const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float r = p[4 * i4 + j];
-                    if (!FOLD_NORM) r = r * norm;
-                    const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
-                    p[4 * i4 + j] = v;
-                    mn = fminf(mn, v);
-                    mx = fmaxf(mx, v);
-                }
-            }
-            mn = wave_min_f(mn);
-            mx = wave_max_f(mx);
-            if (lane == 0) { lred[2 * wave] = mn; lred[2 * wave + 1] = mx; }
-        }
-        __syncthreads();                       // the bias staged above is also complete behind the first barrier
-        if (active) {
-            mn = fminf(mn, lred[2 * (wave ^ 1)]);
-            mx = fmaxf(mx, lred[2 * (wave ^ 1) + 1]);
-            const float lo = q.clip_lo * mn;
-            const float hi = q.clip_hi * mx;
-            float sc = __fdiv_rn(hi - lo, 15.0f);
-            if (!(sc > 0.0f && sc < INFINITY)) sc = 1.0f;
-            const float inv = __fdiv_rn(1.0f, sc);
-            const float nlo = -(lo * inv);
-            int sum = 0;
-            uint32_t words[4];
-#pragma unroll
-            for (int w4 = 0; w4 < 4; ++w4) {
-                uint32_t ev = 0, od = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[8 * w4 + 2 * j], inv, nlo), 0.0f, 15.0f);
-                    const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[8 * w4 + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
-                    ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);
-                    od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
-                }
-                sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
-                sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
-                words[w4] = ev | (od << 4);
-            }
-            *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 1024 * half + 16 * lane) =
-                make_uint4(words[0], words[1], words[2], words[3]);
-            sum = wave_sum_i(sum);
-            if (lane == 0) {
-                if (half == 0) {
-                    basq_tokmeta mt;
-                    mt.scale = sc; mt.lo = lo; mt.rowsum = sum; mt.reserved = 0;
-                    lmeta[t] = mt;
-                } else {
-                    lsum_hi[t] = sum;
-                }
+        if (HAS_BIAS) p2_stage_bias<K>(lbias_s, q.bias, tid, LD_THREADS);   // complete behind the routine's first barrier
+        const P2Meta tm = p2_token_pair<FOLD_NORM, HAS_BIAS, HAS_SCALE>(
+            active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + wave * 512, xch + (wave ^ 1) * 512, lred + 2 * wave,
+            lred + 2 * (wave ^ 1), reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
+            pl.wbase, pl.rbase, [&](const uint32_t (&words)[4]) {
+                *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 1024 * half + 16 * lane) =
+                    make_uint4(words[0], words[1], words[2], words[3]);
+            });
+        if (active && lane == 0) {
+            if (half == 0) {
+                basq_tokmeta mt;
+                mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum; mt.reserved = 0;
+                lmeta[t] = mt;
+            } else {
+                lsum_hi[t] = tm.rowsum;
             }
         }
     } else {

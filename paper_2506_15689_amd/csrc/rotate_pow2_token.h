@@ -319,6 +319,155 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
     return out;
 }
 
+
+// Two wavefronts per token, K = 4096 (for calls with so few tokens that one wave's latency is the whole cost).
+// Wave `half` (0 or 1) takes chunks 4*half .. 4*half+3 through the MFMA and the register stages; the last chunk stage
+// (e11) pairs chunk c of one wave with chunk c of the other, so the two exchange their 32 values per lane through
+// LDS and each keeps one output of every butterfly; after it a wave owns one 2048-channel half (b = half) for the
+// transpose, the remaining stages and the quantiser, and only the token's range is combined across the two.  Every
+// value is produced by the same operations in the same order as in p2_token: same bits.
+//   raw         this wave's four chunks: raw[j] = 16 bytes at channel 512*(4*half + j) + 8*chunk
+//   xch_mine / xch_other   8 * 64 float4 each in LDS: where this wave deposits its values / where its partner does
+//   red_mine / red_other   2 floats each in LDS (min, max)
+//   sink(words) the 32 codes of channels 2048*half + 32*lane .. +31, packed two per byte
+// Calls __syncthreads() twice: every wave of the workgroup calls it, `active` or not.  Returns the token's scale and
+// lower bound and the row sum of THIS wave's half; the caller adds the two halves.
+template <bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
+__device__ __forceinline__ P2Meta p2_token_pair(bool active, int half, const uint4 (&raw)[4], const v8bf (&bop)[2], float* wl,
+                                                float4* xch_mine, const float4* xch_other, float* red_mine,
+                                                const float* red_other, const float4* lbias, const float* act_scale,
+                                                float norm, float clip_lo, float clip_hi, int lane, int wbase, int rbase,
+                                                Sink&& sink) {
+    float d[4][2][4];
+    if (active) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const v8bf aop = __builtin_bit_cast(v8bf, raw[j]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                v4f acc = {0.f, 0.f, 0.f, 0.f};
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[h], acc, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) d[j][h][r] = acc[r];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                BFLY(d[j][h][0], d[j][h][1]);
+                BFLY(d[j][h][2], d[j][h][3]);
+                BFLY(d[j][h][0], d[j][h][2]);
+                BFLY(d[j][h][1], d[j][h][3]);
+            }
+#pragma unroll
+        for (int sft = 1; sft < 4; sft <<= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((j & sft) == 0)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) BFLY(d[j][h][r], d[j + sft][h][r]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                xch_mine[(2 * j + h) * 64 + lane] = make_float4(d[j][h][0], d[j][h][1], d[j][h][2], d[j][h][3]);
+    }
+    __syncthreads();
+    float p[32];
+    float mn = INFINITY, mx = -INFINITY;
+    if (active) {
+        // stage e11: chunk c of the lower wave with chunk c + 4 of the upper one
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 o = xch_other[(2 * j + h) * 64 + lane];
+                const float ov[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) d[j][h][r] = half == 0 ? d[j][h][r] + ov[r] : ov[r] - d[j][h][r];
+            }
+        // transpose of this wave's 2048 channels, as in p2_token
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c01 = 0; c01 < 4; ++c01) {
+                const int r0 = r & 1, r1 = r >> 1;
+                const int addr = (wbase ^ ((r0 << 1) | (r1 << 2))) | (r0 << 5) | (r1 << 6) | (c01 << 9);
+                *reinterpret_cast<float2*>(wl + addr) = make_float2(d[c01][0][r], d[c01][1][r]);
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int qq = 0; qq < 16; ++qq) {
+            const int e1 = qq & 1, e2 = (qq >> 1) & 1, e3 = (qq >> 2) & 1, e4 = qq >> 3;
+            const int addr = (rbase ^ ((e1 << 1) | (e2 << 2))) | (e3 << 7) | (e4 << 8);
+            const float2 v = *reinterpret_cast<const float2*>(wl + addr);
+            const int idx = (e1 << 1) | (e2 << 2) | (e3 << 3) | (e4 << 4);
+            p[idx] = v.x;
+            p[idx | 1] = v.y;
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) if ((i & 8) == 0) BFLY(p[i], p[i | 8]);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[i], p[i | 16]);
+        const int e0 = 2048 * half + 32 * lane;
+#pragma unroll
+        for (int i4 = 0; i4 < 8; ++i4) {
+            float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (HAS_BIAS) bb = lbias[(half * 8 + i4) * 64 + lane];
+            if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(act_scale + e0 + 4 * i4);
+            const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+            const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float r = p[4 * i4 + j];
+                if (!FOLD_NORM) r = r * norm;
+                const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
+                p[4 * i4 + j] = v;
+                mn = fminf(mn, v);
+                mx = fmaxf(mx, v);
+            }
+        }
+        mn = wave_min_f(mn);
+        mx = wave_max_f(mx);
+        if (lane == 0) { red_mine[0] = mn; red_mine[1] = mx; }
+    }
+    __syncthreads();
+    P2Meta out;
+    out.scale = 1.0f; out.lo = 0.0f; out.rowsum = 0;
+    if (active) {
+        mn = fminf(mn, red_other[0]);
+        mx = fmaxf(mx, red_other[1]);
+        const float lo = clip_lo * mn;
+        const float hi = clip_hi * mx;
+        float s = __fdiv_rn(hi - lo, 15.0f);
+        if (!(s > 0.0f && s < INFINITY)) s = 1.0f;
+        const float inv = __fdiv_rn(1.0f, s);
+        const float nlo = -(lo * inv);
+        int sum = 0;
+        uint32_t words[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            uint32_t ev = 0, od = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[8 * w + 2 * j], inv, nlo), 0.0f, 15.0f);
+                const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
+                ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
+                od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
+            }
+            sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
+            sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
+            words[w] = ev | (od << 4);
+        }
+        sink(words);
+        out.scale = s; out.lo = lo; out.rowsum = wave_sum_i(sum);
+    }
+    return out;
+}
+
 }  // namespace
 }  // namespace basq
 
