@@ -36,8 +36,8 @@ MEASURED_TRAFFIC = {
     ("C2", "rotate_quant"): 27564191, ("C2", "gemm"): 170037084, ("C2", "gemm_fp6"): 176944755,
     ("C4", "rotate_quant"): 110548863, ("C4", "gemm"): 176694503, ("C4", "gemm_fp6"): 260240288,
     ("C5", "rotate_quant"): 109842228, ("C5", "gemm"): 945431192, ("C5", "gemm_fp6"): 1294320431,
-    ("C3_M16", "rotate_quant"): 301233, ("C3_M16", "gemm"): 8985923,
-    ("C3_M1", "rotate_quant"): 44642, ("C3_M1", "gemm"): 8616106,
+    ("C3_M16", "rotate_quant"): 400547, ("C3_M16", "gemm"): 8984600,
+    ("C3_M1", "rotate_quant"): 39931, ("C3_M1", "gemm"): 8614970,
 }
 
 
