@@ -10,7 +10,7 @@
 //
 //   phase 0   every lane requests all of its 16-byte weight pieces (streaming layout) and its epilogue constants
 //   phase 1   wave w rotates and quantises tokens w, w+4, ...; codes and token records go to LDS
-//             (one or two tokens of K = 4096: two waves per token, see "pair mode" below)
+//             (one or two tokens of K = 4096, one of K = 8192: several waves per token, see "split mode" below)
 //   phase 2   16 x 16 x 64 int8 MFMA on the weights (registers) and the codes (LDS), cross-wave reduction,
 //             de-quantisation, bf16 store -- as in the weight-streaming kernel
 #include "rotate_pow2_token.h"
@@ -37,12 +37,12 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     __shared__ __attribute__((aligned(16))) float lbias_s[HAS_BIAS ? K : 4];
     __shared__ __attribute__((aligned(16))) uint8_t xq[LD_MAX_TOKENS * XQ_STRIDE];
     __shared__ basq_tokmeta lmeta[LD_MAX_TOKENS];
-    __shared__ int lsum_hi[LD_MAX_TOKENS];               // pair mode: the row sum of a token's upper 2048 channels
+    __shared__ int lsum_hi[LD_MAX_TOKENS];               // split mode: the row sums of a token's blocks other than the first
     __shared__ int part[LD_WAVES][LD_ROWS * 16];
-    // pair mode (K = 4096, at most two tokens): two waves share a token, see below
-    constexpr bool CAN_PAIR = NC == 8;
-    __shared__ __attribute__((aligned(16))) float4 xch[CAN_PAIR ? LD_WAVES * 8 * 64 : 1];
-    __shared__ float lred[CAN_PAIR ? LD_WAVES * 2 : 1];
+    // split mode (K = 4096: at most two tokens, two waves each; K = 8192: one token on all four waves), see below
+    constexpr int NWAY = NC / 4;                         // waves per token in split mode
+    __shared__ __attribute__((aligned(16))) float4 xch[LD_WAVES * 8 * 64];
+    __shared__ float lred[LD_WAVES * 2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int M = (int)g.M;
@@ -75,11 +75,11 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
 #pragma unroll
         for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
     };
-    // Pair mode: with one or two tokens of K = 4096, two waves share a token (p2_token_pair: same bits).
-    const bool pair_mode = CAN_PAIR && M <= 2;                          // uniform over the grid
-    if (pair_mode) {
+    // Split mode: with so few tokens that every token can have NWAY waves, they share it (p2_token_split: same bits).
+    const bool split_mode = M * NWAY <= LD_WAVES;                       // uniform over the grid
+    if (split_mode) {
         if (tid < LD_MAX_TOKENS) lsum_hi[tid] = 0;
-        const int t = wave >> 1, half = wave & 1;
+        const int t = wave / NWAY, half = wave % NWAY;                  // token, and this wave's 2048-channel block of it
         const bool active = t < M;
         uint4 raw4[4] = {};
         if (active) {
@@ -88,9 +88,9 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
             for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
         }
         if (HAS_BIAS) p2_stage_bias<K>(lbias_s, q.bias, tid, LD_THREADS);   // complete behind the routine's first barrier
-        const P2Meta tm = p2_token_pair<FOLD_NORM, HAS_BIAS, HAS_SCALE>(
-            active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + wave * 512, xch + (wave ^ 1) * 512, lred + 2 * wave,
-            lred + 2 * (wave ^ 1), reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
+        const P2Meta tm = p2_token_split<NWAY, FOLD_NORM, HAS_BIAS, HAS_SCALE>(
+            active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + t * (NWAY * 512), lred + t * (NWAY * 2),
+            reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
             pl.wbase, pl.rbase, [&](const uint32_t (&words)[4]) {
                 *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 1024 * half + 16 * lane) =
                     make_uint4(words[0], words[1], words[2], words[3]);
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
                 mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum; mt.reserved = 0;
                 lmeta[t] = mt;
             } else {
-                lsum_hi[t] = tm.rowsum;
+                atomicAdd(&lsum_hi[t], tm.rowsum);       // LDS integer adds: any order gives the same sum
             }
         }
     } else {

@@ -320,24 +320,24 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
 }
 
 
-// Two wavefronts per token, K = 4096 (for calls with so few tokens that one wave's latency is the whole cost).
-// Wave `half` (0 or 1) takes chunks 4*half .. 4*half+3 through the MFMA and the register stages; the last chunk stage
-// (e11) pairs chunk c of one wave with chunk c of the other, so the two exchange their 32 values per lane through
-// LDS and each keeps one output of every butterfly; after it a wave owns one 2048-channel half (b = half) for the
-// transpose, the remaining stages and the quantiser, and only the token's range is combined across the two.  Every
-// value is produced by the same operations in the same order as in p2_token: same bits.
-//   raw         this wave's four chunks: raw[j] = 16 bytes at channel 512*(4*half + j) + 8*chunk
-//   xch_mine / xch_other   8 * 64 float4 each in LDS: where this wave deposits its values / where its partner does
-//   red_mine / red_other   2 floats each in LDS (min, max)
-//   sink(words) the 32 codes of channels 2048*half + 32*lane .. +31, packed two per byte
+// NWAY wavefronts per token: two for K = 4096, four for K = 8192 (for calls with so few tokens that one wave's
+// latency is the whole cost).  Wave `part` (0 .. NWAY-1) takes chunks 4*part .. 4*part+3 through the MFMA and the
+// register stages.  The last one or two chunk stages (e11; e11 and e12) pair chunk c of one wave with chunk c of
+// another, so the waves exchange their 32 values per lane through LDS and each keeps its own output of the
+// butterflies; after that a wave owns one 2048-channel block (hf = part / 2, b = part % 2) for the transpose, the
+// remaining stages and the quantiser, and only the token's range is combined across the waves.  Every value is
+// produced by the same operations in the same order as in p2_token: same bits.
+//   raw         this wave's four chunks: raw[j] = 16 bytes at channel 512*(4*part + j) + 8*chunk
+//   xch         NWAY * 512 float4 in LDS shared by the token's waves;  red: NWAY * 2 floats likewise
+//   sink(words) the 32 codes of channels 2048*part + 32*lane .. +31, packed two per byte
 // Calls __syncthreads() twice: every wave of the workgroup calls it, `active` or not.  Returns the token's scale and
-// lower bound and the row sum of THIS wave's half; the caller adds the two halves.
-template <bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
-__device__ __forceinline__ P2Meta p2_token_pair(bool active, int half, const uint4 (&raw)[4], const v8bf (&bop)[2], float* wl,
-                                                float4* xch_mine, const float4* xch_other, float* red_mine,
-                                                const float* red_other, const float4* lbias, const float* act_scale,
-                                                float norm, float clip_lo, float clip_hi, int lane, int wbase, int rbase,
-                                                Sink&& sink) {
+// lower bound and the row sum of THIS wave's block; the caller adds the blocks.
+template <int NWAY, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
+__device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const uint4 (&raw)[4], const v8bf (&bop)[2], float* wl,
+                                                 float4* xch, float* red, const float4* lbias, const float* act_scale,
+                                                 float norm, float clip_lo, float clip_hi, int lane, int wbase, int rbase,
+                                                 Sink&& sink) {
+    static_assert(NWAY == 2 || NWAY == 4, "two waves for K = 4096, four for K = 8192");
     float d[4][2][4];
     if (active) {
 #pragma unroll
@@ -373,21 +373,35 @@ __device__ __forceinline__ P2Meta p2_token_pair(bool active, int half, const uin
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                xch_mine[(2 * j + h) * 64 + lane] = make_float4(d[j][h][0], d[j][h][1], d[j][h][2], d[j][h][3]);
+                xch[(part * 8 + 2 * j + h) * 64 + lane] = make_float4(d[j][h][0], d[j][h][1], d[j][h][2], d[j][h][3]);
     }
     __syncthreads();
     float p[32];
     float mn = INFINITY, mx = -INFINITY;
     if (active) {
-        // stage e11: chunk c of the lower wave with chunk c + 4 of the upper one
+        // stage e11 pairs wave w with w ^ 1 (lower index: sum, upper: difference); stage e12 then pairs w with w ^ 2
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const float4 o = xch_other[(2 * j + h) * 64 + lane];
-                const float ov[4] = {o.x, o.y, o.z, o.w};
+                const float4 o1 = xch[((part ^ 1) * 8 + 2 * j + h) * 64 + lane];
+                const float ov1[4] = {o1.x, o1.y, o1.z, o1.w};
+                if (NWAY == 2) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) d[j][h][r] = half == 0 ? d[j][h][r] + ov[r] : ov[r] - d[j][h][r];
+                    for (int r = 0; r < 4; ++r) d[j][h][r] = (part & 1) == 0 ? d[j][h][r] + ov1[r] : ov1[r] - d[j][h][r];
+                } else {
+                    const float4 o2 = xch[((part ^ 2) * 8 + 2 * j + h) * 64 + lane];
+                    const float4 o3 = xch[((part ^ 3) * 8 + 2 * j + h) * 64 + lane];
+                    const float ov2[4] = {o2.x, o2.y, o2.z, o2.w};
+                    const float ov3[4] = {o3.x, o3.y, o3.z, o3.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // e11 in this wave's pair and in the pair it meets at e12 (same position within the pair)
+                        const float mine = (part & 1) == 0 ? d[j][h][r] + ov1[r] : ov1[r] - d[j][h][r];
+                        const float theirs = (part & 1) == 0 ? ov2[r] + ov3[r] : ov3[r] - ov2[r];
+                        d[j][h][r] = (part & 2) == 0 ? mine + theirs : theirs - mine;
+                    }
+                }
             }
         // transpose of this wave's 2048 channels, as in p2_token
 #pragma unroll
@@ -412,11 +426,11 @@ __device__ __forceinline__ P2Meta p2_token_pair(bool active, int half, const uin
         for (int i = 0; i < 32; ++i) if ((i & 8) == 0) BFLY(p[i], p[i | 8]);
 #pragma unroll
         for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[i], p[i | 16]);
-        const int e0 = 2048 * half + 32 * lane;
+        const int e0 = 2048 * part + 32 * lane;
 #pragma unroll
         for (int i4 = 0; i4 < 8; ++i4) {
             float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (HAS_BIAS) bb = lbias[(half * 8 + i4) * 64 + lane];
+            if (HAS_BIAS) bb = lbias[(part * 8 + i4) * 64 + lane];
             if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(act_scale + e0 + 4 * i4);
             const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
             const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
@@ -432,14 +446,17 @@ __device__ __forceinline__ P2Meta p2_token_pair(bool active, int half, const uin
         }
         mn = wave_min_f(mn);
         mx = wave_max_f(mx);
-        if (lane == 0) { red_mine[0] = mn; red_mine[1] = mx; }
+        if (lane == 0) { red[2 * part] = mn; red[2 * part + 1] = mx; }
     }
     __syncthreads();
     P2Meta out;
     out.scale = 1.0f; out.lo = 0.0f; out.rowsum = 0;
     if (active) {
-        mn = fminf(mn, red_other[0]);
-        mx = fmaxf(mx, red_other[1]);
+#pragma unroll
+        for (int o = 1; o < NWAY; ++o) {
+            mn = fminf(mn, red[2 * (part ^ o)]);
+            mx = fmaxf(mx, red[2 * (part ^ o) + 1]);
+        }
         const float lo = clip_lo * mn;
         const float hi = clip_hi * mx;
         float s = __fdiv_rn(hi - lo, 15.0f);

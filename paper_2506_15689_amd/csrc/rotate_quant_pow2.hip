@@ -130,47 +130,52 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
     }
 }
 
-// Few tokens of K = 4096: two waves per token (p2_token_pair), two tokens per workgroup, one round.  A call this
-// small is all latency -- one wave needs about 2.8 us for a token -- and the pair roughly halves the chain.
-template <bool HAS_BIAS, bool HAS_SCALE>
-__global__ __launch_bounds__(256) void rotate_quant_pow2_pair_kernel(RotateQuantArgs a, float norm) {
-    constexpr int K = 4096;
+// Few tokens: NWAY = NC / 4 waves per token (p2_token_split; two for K = 4096, four for K = 8192), 4 / NWAY tokens per
+// workgroup, one round.  A call this small is all latency -- one wave needs about 2.8 us (5.6 us) for a token -- and
+// the split divides the chain.
+template <int NC, bool HAS_BIAS, bool HAS_SCALE>
+__global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuantArgs a, float norm) {
+    constexpr int K = 512 * NC, NWAY = NC / 4, TOKENS = 4 / NWAY;
     __shared__ __attribute__((aligned(16))) float tr[4 * P2_LDS_WORDS];
     __shared__ __attribute__((aligned(16))) float lbias_s[HAS_BIAS ? K : 4];
     __shared__ __attribute__((aligned(16))) float4 xch[4 * 512];
     __shared__ float lred[8];
-    __shared__ int lsum[2];
+    __shared__ int lsum[TOKENS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tl = wave >> 1, half = wave & 1;
-    const int64_t m = (int64_t)blockIdx.x * 2 + tl;
+    const int tl = wave / NWAY, part = wave % NWAY;
+    const int64_t m = (int64_t)blockIdx.x * TOKENS + tl;
     const bool active = m < a.M;
+    if (tid < TOKENS) lsum[tid] = 0;
     v8bf bop[2];
-    p2_make_bop<8, true>(lane, bop);
+    p2_make_bop<NC, NC == 8>(lane, bop);
     const P2Lane pl = p2_lane(lane);
     uint4 raw4[4] = {};
     if (active) {
-        const uint16_t* x = a.X + m * a.ldx + 8 * pl.chunk + 2048 * half;
+        const uint16_t* x = a.X + m * a.ldx + 8 * pl.chunk + 2048 * part;
 #pragma unroll
         for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
     }
     if (HAS_BIAS) p2_stage_bias<K>(lbias_s, a.bias, tid, 256);          // complete behind the routine's first barrier
-    const P2Meta tm = p2_token_pair<true, HAS_BIAS, HAS_SCALE>(
-        active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + wave * 512, xch + (wave ^ 1) * 512, lred + 2 * wave,
-        lred + 2 * (wave ^ 1), reinterpret_cast<const float4*>(lbias_s), a.act_scale, norm, a.clip_lo, a.clip_hi, lane,
+    const P2Meta tm = p2_token_split<NWAY, NC == 8, HAS_BIAS, HAS_SCALE>(
+        active, part, raw4, bop, tr + wave * P2_LDS_WORDS, xch + tl * (NWAY * 512), lred + tl * (NWAY * 2),
+        reinterpret_cast<const float4*>(lbias_s), a.act_scale, norm, a.clip_lo, a.clip_hi, lane,
         pl.wbase, pl.rbase, [&](const uint32_t (&words)[4]) {
-            nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * half + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
+            nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * part + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
         });
-    if (active && half == 1 && lane == 0) lsum[tl] = tm.rowsum;
+    if (active && part != 0 && lane == 0) atomicAdd(&lsum[tl], tm.rowsum);    // LDS integer adds: order-free
     __syncthreads();
-    if (active && half == 0 && lane == 0) {
+    if (active && part == 0 && lane == 0) {
         basq_tokmeta mt;
         mt.scale = tm.scale; mt.lo = tm.lo; mt.rowsum = tm.rowsum + lsum[tl]; mt.reserved = 0;
         a.meta[m] = mt;
     }
 }
 
-#ifndef P2_PAIR_MAX_TOKENS
-#define P2_PAIR_MAX_TOKENS 512
+#ifndef P2_SPLIT_MAX_TOKENS_4096
+#define P2_SPLIT_MAX_TOKENS_4096 512      // measured: 4.6-5.6 us against 5.4-6.3 us up to here, slower from 1024 on
+#endif
+#ifndef P2_SPLIT_MAX_TOKENS_8192
+#define P2_SPLIT_MAX_TOKENS_8192 256
 #endif
 
 template <int NC, bool FOLD, bool HB, bool HS, bool RO, bool GR, int WAVES, bool STAGE>
@@ -188,9 +193,11 @@ int launch_flags(const RotateQuantArgs& a, hipStream_t s, float norm) {
     if (a.rot_out && grouped) return launch_one<NC, FOLD, HB, HS, true, true, 4, false>(a, s, norm);
     if (grouped) return launch_one<NC, FOLD, HB, HS, false, true, 4, false>(a, s, norm);
     if (a.rot_out) return launch_one<NC, FOLD, HB, HS, true, false, 4, false>(a, s, norm);
-    if (NC == 8 && !a.Aq6 && a.M <= P2_PAIR_MAX_TOKENS) {
-        hipLaunchKernelGGL((rotate_quant_pow2_pair_kernel<HB, HS>), dim3((unsigned)((a.M + 1) / 2)), dim3(256), 0, s, a, norm);
-        return check_hip(hipGetLastError(), "rotate_quant (pow2, pair) launch");
+    if (!a.Aq6 && a.M <= (NC == 8 ? P2_SPLIT_MAX_TOKENS_4096 : P2_SPLIT_MAX_TOKENS_8192)) {
+        constexpr int TOKENS = 16 / NC;                                   // per workgroup of four waves
+        hipLaunchKernelGGL((rotate_quant_pow2_split_kernel<NC, HB, HS>), dim3((unsigned)((a.M + TOKENS - 1) / TOKENS)),
+                           dim3(256), 0, s, a, norm);
+        return check_hip(hipGetLastError(), "rotate_quant (pow2, split) launch");
     }
     // measured: the tail stage pays from about 32768 tokens on.  Without it, eight waves per workgroup help from 2048
     // tokens (fewer workgroups stage the bias; below that, four-wave workgroups spread the tokens over more compute

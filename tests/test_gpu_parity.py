@@ -114,13 +114,14 @@ def test_decode_ragged(M, K, N):
 @pytest.mark.parametrize("M,K,N,scaled,biased", [(1, 8192, 24, False, False), (4, 8192, 100, True, True), (3, 8192, 48, False, True), (16, 8192, 48, False, False),
                                                  (3, 4096, 40, True, True), (4, 4096, 4096, False, True), (2, 4096, 17, True, False),
                                                  (5, 4096, 4096, False, True), (1, 4096, 4096, False, False), (1, 4096, 40, True, False),
-                                                 (2, 4096, 264, False, True), (2, 4096, 4096, True, True)])
+                                                 (2, 4096, 264, False, True), (2, 4096, 4096, True, True), (1, 8192, 100, True, False)])
 def test_decode_one_launch(M, K, N, scaled, biased):
     """Calls of at most 4 tokens with rot_size = K in {4096, 8192}, N <= 4096 and the streaming weight layout run
     the whole layer in one kernel (basq_linear_fused); run_case checks its output against the two-call path bit
     for bit, and that path against the oracle.  With and without s^a and the bias, ragged N; the cases above 4
-    tokens take the two-kernel path on the same shapes.  One or two tokens of K = 4096 run two waves per token
-    (the halves exchange one butterfly stage, the range and the row sum through LDS)."""
+    tokens take the two-kernel path on the same shapes.  One or two tokens of K = 4096 run two waves per token, one token
+    of K = 8192 four (they exchange one or two butterfly stages, the range and the row sum through LDS); the
+    two-kernel path splits tokens the same way up to a few hundred tokens."""
     lay = si.make_tiny(M, K, N, seed=M + K + N)
     sa = np.random.default_rng(M + N).uniform(0.7, 1.5, K).astype(np.float32) if scaled else None
     run_case(lay, act_scale=sa, use_bias=biased, use_out_bias=biased, use_blas_gemm=True)
