@@ -196,6 +196,9 @@ static void launch_gemv_layout(const GemmArgs& a, hipStream_t s) {
         const bool deep = a.K / 128 > 32;
         // two tiles per workgroup once the activations weigh in (more than 8 tokens) and the chip stays filled
         if (a.M > 8 && blocks16 >= 4 * 256) launch_gemv_cfg<SL, 8, 2, 1>(a, s, blocks16);
+        // 65 .. 112 chunks per row (K = 14336): all of a lane's loads in one batch instead of one and a ragged one
+        // (measured 8.0 us against 8.8 us on N = 4096)
+        else if (a.K / 128 > 64 && a.K / 128 <= 112) launch_gemv_cfg<SL, 28, 1, 1>(a, s, blocks16);
         else if (deep) launch_gemv_cfg<SL, 16, 1, 1>(a, s, blocks16);
         else launch_gemv_cfg<SL, 8, 1, 1>(a, s, blocks16);
     } else if (a.M <= 32) {
