@@ -91,7 +91,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
         const P2Meta tm = p2_token_split<NWAY, FOLD_NORM, HAS_BIAS, HAS_SCALE>(
             active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + t * (NWAY * 512), lred + t * (NWAY * 2),
             reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
-            pl.wbase, pl.rbase, [&](const uint32_t (&words)[4]) {
+            pl.wbase, pl.rbase, [&](const uint32_t (&words)[4], const v16f&, const v16f&) {
                 *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 1024 * half + 16 * lane) =
                     make_uint4(words[0], words[1], words[2], words[3]);
             });

@@ -329,7 +329,8 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
 // produced by the same operations in the same order as in p2_token: same bits.
 //   raw         this wave's four chunks: raw[j] = 16 bytes at channel 512*(4*part + j) + 8*chunk
 //   xch         NWAY * 512 float4 in LDS shared by the token's waves;  red: NWAY * 2 floats likewise
-//   sink(words) the 32 codes of channels 2048*part + 32*lane .. +31, packed two per byte
+//   sink(words, te, to) the 32 codes of channels 2048*part + 32*lane .. +31, packed two per byte, and the clamped
+//               values before rounding (even / odd channels) as in p2_token
 // Calls __syncthreads() twice: every wave of the workgroup calls it, `active` or not.  Returns the token's scale and
 // lower bound and the row sum of THIS wave's block; the caller adds the blocks.
 template <int NWAY, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
@@ -465,6 +466,7 @@ __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const ui
         const float nlo = -(lo * inv);
         int sum = 0;
         uint32_t words[4];
+        v16f te, to;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             uint32_t ev = 0, od = 0;
@@ -474,12 +476,14 @@ __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const ui
                 const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
                 ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
                 od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
+                te[4 * w + j] = t0;
+                to[4 * w + j] = t1;
             }
             sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
             sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
             words[w] = ev | (od << 4);
         }
-        sink(words);
+        sink(words, te, to);
         out.scale = s; out.lo = lo; out.rowsum = wave_sum_i(sum);
     }
     return out;

@@ -159,8 +159,16 @@ __global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuan
     const P2Meta tm = p2_token_split<NWAY, NC == 8, HAS_BIAS, HAS_SCALE>(
         active, part, raw4, bop, tr + wave * P2_LDS_WORDS, xch + tl * (NWAY * 512), lred + tl * (NWAY * 2),
         reinterpret_cast<const float4*>(lbias_s), a.act_scale, norm, a.clip_lo, a.clip_hi, lane,
-        pl.wbase, pl.rbase, [&](const uint32_t (&words)[4]) {
+        pl.wbase, pl.rbase, [&](const uint32_t (&words)[4], const v16f& te, const v16f& to) {
             nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * part + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
+            if (a.Aq6) {      // the fp6 copy, as in the one-wave kernel: group 64*part + lane of the token
+                const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(te, to, 8.0f);
+                const int g = 64 * part + lane, f = g & 3, r = (int)(m & 31);
+                uint8_t* blk = a.Aq6 + ((int64_t)(g >> 2) * ((a.M + 31) >> 5) + (m >> 5)) * 3072;
+                *reinterpret_cast<uint4*>(blk + 64 * r + 16 * (f ^ ((r >> 2) & 3))) =
+                    make_uint4((uint32_t)f6[0], (uint32_t)f6[1], (uint32_t)f6[2], (uint32_t)f6[3]);
+                *reinterpret_cast<uint2*>(blk + 2048 + 256 * f + 8 * r) = make_uint2((uint32_t)f6[4], (uint32_t)f6[5]);
+            }
         });
     if (active && part != 0 && lane == 0) atomicAdd(&lsum[tl], tm.rowsum);    // LDS integer adds: order-free
     __syncthreads();
@@ -193,7 +201,7 @@ int launch_flags(const RotateQuantArgs& a, hipStream_t s, float norm) {
     if (a.rot_out && grouped) return launch_one<NC, FOLD, HB, HS, true, true, 4, false>(a, s, norm);
     if (grouped) return launch_one<NC, FOLD, HB, HS, false, true, 4, false>(a, s, norm);
     if (a.rot_out) return launch_one<NC, FOLD, HB, HS, true, false, 4, false>(a, s, norm);
-    if (!a.Aq6 && a.M <= (NC == 8 ? P2_SPLIT_MAX_TOKENS_4096 : P2_SPLIT_MAX_TOKENS_8192)) {
+    if (a.M <= (NC == 8 ? P2_SPLIT_MAX_TOKENS_4096 : P2_SPLIT_MAX_TOKENS_8192)) {
         constexpr int TOKENS = 16 / NC;                                   // per workgroup of four waves
         hipLaunchKernelGGL((rotate_quant_pow2_split_kernel<NC, HB, HS>), dim3((unsigned)((a.M + TOKENS - 1) / TOKENS)),
                            dim3(256), 0, s, a, norm);
