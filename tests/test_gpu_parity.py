@@ -41,8 +41,11 @@ def test_c1_full():
     run_case(si.make_layer(si.CONFIGS["C1"]))
 
 
-@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (161, 256, 40), (129, 4096, 96), (200, 512, 1152), (260, 1024, 1100)])
+@pytest.mark.parametrize("M,K,N", [(200, 2048, 328), (130, 512, 136), (161, 256, 40), (129, 4096, 96), (200, 512, 1152), (260, 1024, 1100),
+                                   (201, 8192, 72), (300, 8192, 40), (600, 4096, 72)])
 def test_ragged_multi_tile(M, K, N):
+    """(The K = 4096 / 8192 cases also cover the rotate+quant kernels on both sides of their token-count switches:
+    several waves per token up to 512 / 256 tokens, one wave per token beyond, each with the fp6 copy.)"""
     run_case(si.make_tiny(M, K, N, seed=M))
 
 
