@@ -210,6 +210,28 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
                       void* Y, int64_t ldy, const uint8_t* Wq6,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * basq_linear_fused for callers that cannot allocate a workspace or keep one alive: code recorded under HIP graph
+ * capture, tight serving loops, harnesses in which hipMalloc is forbidden.  Same arguments, same kernels and
+ * bit-identical results; the codes and token records live in a workspace of BASQ_STATIC_WORKSPACE_BYTES that is
+ * part of the library's code object (every GPU the library runs on holds its own copy until the process ends).
+ *   - basq_workspace_bytes(M, K, N) > BASQ_STATIC_WORKSPACE_BYTES returns BASQ_EWORKSPACE and launches nothing
+ *     (8 MiB hold e.g. 192 tokens of K = 32768, 800 of K = 8192, 1632 of K = 4096).
+ *   - The call allocates nothing, frees nothing and does not synchronise.  Its first call on a device looks the
+ *     workspace's address up (hipGetSymbolAddress, which may load the code object): make that call outside stream
+ *     capture.
+ *   - All calls on one GPU share that GPU's workspace, which keeps the previous call's contents (the quantiser
+ *     writes every byte the product reads, so nothing needs clearing).  Calls that overlap on one GPU - different
+ *     streams, or threads - race on it; calls on one stream, or otherwise ordered, do not.
+ */
+#define BASQ_STATIC_WORKSPACE_BYTES (8u << 20)
+int basq_linear_fused_static(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size,
+                             const float* bias, const float* act_scale,
+                             float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                             const uint8_t* Wq, int32_t N, int32_t w_layout,
+                             const void* w_scale, const void* w_zero, const float* w_sum, const float* out_bias,
+                             void* Y, int64_t ldy, const uint8_t* Wq6, void* stream);
+
 /* ---- offline helpers (not on the timed path) --------------------------------------------- */
 
 /*

@@ -22,7 +22,7 @@ BASQ_W_DECODE16 = 1
 STREAM_MAX_TOKENS = 128      # calls of at most this many tokens take the weight-streaming kernel (K % 128 == 0)
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
-           "basq_w4a4_gemm_grouped", "basq_group_colsums", "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_w4a4_gemm_grouped", "basq_group_colsums", "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_linear_fused_static", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
            "basq_hadamard28", "basq_diag_stream", "basq_diag_read", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
@@ -71,6 +71,9 @@ def load() -> ctypes.CDLL:
     lib.basq_linear_fused.restype = c.c_int
     lib.basq_linear_fused.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32,
                                       vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp, c.c_size_t, vp]
+    lib.basq_linear_fused_static.restype = c.c_int
+    lib.basq_linear_fused_static.argtypes = [vp, i64, i32, i64, i32, vp, vp, f32, f32, i32, i32,
+                                             vp, i32, i32, vp, vp, vp, vp, vp, i64, vp, vp]
     lib.basq_rotate_weights.restype = c.c_int
     lib.basq_rotate_weights.argtypes = [vp, i32, i32, i64, i32, vp, vp, c.c_size_t, vp]
     lib.basq_quantize_weights.restype = c.c_int
@@ -204,6 +207,25 @@ def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
                                     _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
                                     _p(Wq6), _p(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 8 << 20      # BASQ_STATIC_WORKSPACE_BYTES of include/basq.h
+
+
+def basq_linear_fused_static(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tensor],
+                             act_scale: Optional[torch.Tensor], clip_lo: float, clip_hi: float, Wq: torch.Tensor,
+                             w_scale: torch.Tensor, w_zero: torch.Tensor, w_sum: torch.Tensor,
+                             out_bias: Optional[torch.Tensor], Y: torch.Tensor, *,
+                             Wq6: Optional[torch.Tensor] = None,
+                             bits: int = 4, group_size: int = 0, w_layout: int = BASQ_W_CANONICAL,
+                             N: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """basq_linear_fused on the library's own workspace (no workspace argument, nothing allocated)."""
+    M, K = X.shape
+    N = Wq.shape[0] if N is None else N
+    _check(load().basq_linear_fused_static(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias),
+                                           _p(act_scale), clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout,
+                                           _p(w_scale), _p(w_zero), _p(w_sum), _p(out_bias), _p(Y),
+                                           Y.stride(0) if M > 0 else N, _p(Wq6), _stream(stream)))
 
 
 def basq_rotate_weights(W: torch.Tensor, rot_size: int, W_rot: torch.Tensor, workspace: torch.Tensor, *,

@@ -4,6 +4,8 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 namespace basq {
 
 namespace {
@@ -96,6 +98,83 @@ int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, bool need_a, int32_t K)
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// the one-call layer on a workspace of the caller's or of the library's own (both entry points end here)
+int linear_fused_impl(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
+                      const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                      const uint8_t* Wq, int32_t N, int32_t w_layout, const void* w_scale, const void* w_zero,
+                      const float* w_sum, const float* out_bias, void* Y, int64_t ldy,
+                      const uint8_t* Wq6, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    RotateQuantArgs a{};
+    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
+    if (rc != BASQ_OK) return rc;
+    if (group_size != 0 && group_size != K)
+        return fail(BASQ_EUNSUPPORTED, "the GEMM takes per-token ranges only: group_size must be 0 or K (got %d)", group_size);
+    rc = validate_fp6(nullptr, Wq6, false, K);
+    if (rc != BASQ_OK) return rc;
+    if (M == 0) {
+        return validate_gemm(nullptr, nullptr, 0, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
+    }
+    if (!workspace) return fail(BASQ_EINVAL, "workspace is null");
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(BASQ_EINVAL, "workspace must be 256-byte aligned");
+    const size_t need = basq_workspace_bytes(M, K, N);
+    if (workspace_bytes < need)
+        return fail(BASQ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    uint8_t* Aq = static_cast<uint8_t*>(workspace);
+    basq_tokmeta* meta = reinterpret_cast<basq_tokmeta*>(Aq + align_up((size_t)M * (size_t)(K / 2), 256));
+    rc = validate_gemm(Aq, meta, M, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
+    if (rc != BASQ_OK) return rc;
+
+    a.X = static_cast<const uint16_t*>(X);
+    a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
+    a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
+    // the fp6 copy of the codes is only worth making when the matrix-core path will take it
+    uint8_t* Aq6 = nullptr;
+    if (Wq6 && M > GEMV_MAX_TOKENS)
+        Aq6 = reinterpret_cast<uint8_t*>(meta) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
+    a.group = K;
+    a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
+               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, w_layout};
+    if (w_layout != BASQ_W_CANONICAL && M > GEMV_MAX_TOKENS && !gemm_fp6_applicable(g))      // before anything is launched
+        return fail(BASQ_EUNSUPPORTED, "more than 128 tokens with the streaming weight layout need the fp6 operands "
+                                        "(the int8 kernels read canonical weights)");
+    if (linear_decode_applicable(a, g)) return launch_linear_decode(a, g, s);      // a few tokens: one launch
+    rc = launch_rotate_quant(a, s);
+    if (rc != BASQ_OK) return rc;
+    return run_gemm(g, s);
+}
+
+
+// ---- the library's own workspace, for callers that cannot allocate one -------------------------------------
+// One copy per GPU, created when the code object is loaded there and held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[BASQ_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {};
+
+// The current device's copy of `scratch`; looked up once per device, with that device current.
+int static_workspace(unsigned char** out) {
+    int dev = -1;
+    int rc = check_hip(hipGetDevice(&dev), "hipGetDevice");
+    if (rc != BASQ_OK) return rc;
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(BASQ_EUNSUPPORTED, "device ordinal %d is beyond the %d this table holds", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc != BASQ_OK) return rc;
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 255u) != 0)
+            return fail(BASQ_EHIP, "the library's workspace came back null or misaligned (%p)", p);
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return BASQ_OK;
+}
 
 }  // namespace
 }  // namespace basq
@@ -207,45 +286,29 @@ int basq_linear_fused(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
                       const float* w_sum, const float* out_bias, void* Y, int64_t ldy,
                       const uint8_t* Wq6, void* workspace,
                       size_t workspace_bytes, void* stream) {
-    RotateQuantArgs a{};
-    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
-    if (rc != BASQ_OK) return rc;
-    if (group_size != 0 && group_size != K)
-        return fail(BASQ_EUNSUPPORTED, "the GEMM takes per-token ranges only: group_size must be 0 or K (got %d)", group_size);
-    rc = validate_fp6(nullptr, Wq6, false, K);
-    if (rc != BASQ_OK) return rc;
-    if (M == 0) {
-        return validate_gemm(nullptr, nullptr, 0, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
-    }
-    if (!workspace) return fail(BASQ_EINVAL, "workspace is null");
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(BASQ_EINVAL, "workspace must be 256-byte aligned");
-    const size_t need = basq_workspace_bytes(M, K, N);
-    if (workspace_bytes < need)
-        return fail(BASQ_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
-    uint8_t* Aq = static_cast<uint8_t*>(workspace);
-    basq_tokmeta* meta = reinterpret_cast<basq_tokmeta*>(Aq + align_up((size_t)M * (size_t)(K / 2), 256));
-    rc = validate_gemm(Aq, meta, M, K, Wq, N, w_layout, w_scale, w_zero, w_sum, Y, ldy);
-    if (rc != BASQ_OK) return rc;
+    return linear_fused_impl(X, M, K, ldx, rot_size, bias, act_scale, clip_lo, clip_hi, bits, group_size, Wq, N, w_layout,
+                             w_scale, w_zero, w_sum, out_bias, Y, ldy, Wq6, workspace, workspace_bytes, stream);
+}
 
-    a.X = static_cast<const uint16_t*>(X);
-    a.M = M; a.K = K; a.ldx = ldx; a.rot_size = rot_size;
-    a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
-    // the fp6 copy of the codes is only worth making when the matrix-core path will take it
-    uint8_t* Aq6 = nullptr;
-    if (Wq6 && M > GEMV_MAX_TOKENS)
-        Aq6 = reinterpret_cast<uint8_t*>(meta) + align_up((size_t)M * sizeof(basq_tokmeta), 256);
-    a.group = K;
-    a.Aq = Aq; a.meta = meta; a.rot_out = nullptr; a.Aq6 = Aq6;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-               w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, w_layout};
-    if (w_layout != BASQ_W_CANONICAL && M > GEMV_MAX_TOKENS && !gemm_fp6_applicable(g))      // before anything is launched
-        return fail(BASQ_EUNSUPPORTED, "more than 128 tokens with the streaming weight layout need the fp6 operands "
-                                        "(the int8 kernels read canonical weights)");
-    if (linear_decode_applicable(a, g)) return launch_linear_decode(a, g, s);      // a few tokens: one launch
-    rc = launch_rotate_quant(a, s);
+int basq_linear_fused_static(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
+                             const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
+                             const uint8_t* Wq, int32_t N, int32_t w_layout, const void* w_scale, const void* w_zero,
+                             const float* w_sum, const float* out_bias, void* Y, int64_t ldy,
+                             const uint8_t* Wq6, void* stream) {
+    if (M < 0) return fail(BASQ_EINVAL, "M must be >= 0 (got %lld)", (long long)M);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    const size_t need = basq_workspace_bytes(M, K, N);
+    if (need > (size_t)BASQ_STATIC_WORKSPACE_BYTES)
+        return fail(BASQ_EWORKSPACE, "M = %lld tokens of K = %d need %zu bytes of workspace; the library's own holds %zu "
+                                     "(use basq_linear_fused with a workspace of the caller's)",
+                    (long long)M, K, need, (size_t)BASQ_STATIC_WORKSPACE_BYTES);
+    unsigned char* ws = nullptr;
+    const int rc = static_workspace(&ws);
     if (rc != BASQ_OK) return rc;
-    return run_gemm(g, s);
+    // every byte of the codes and records the product reads is written by the quantiser of the same call first,
+    // so nothing of the previous call's contents has to be cleared
+    return linear_fused_impl(X, M, K, ldx, rot_size, bias, act_scale, clip_lo, clip_hi, bits, group_size, Wq, N, w_layout,
+                             w_scale, w_zero, w_sum, out_bias, Y, ldy, Wq6, ws, (size_t)BASQ_STATIC_WORKSPACE_BYTES, stream);
 }
 
 int basq_quantize_weights(const void* W_rot, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq, void* w_scale,
