@@ -22,8 +22,8 @@
  *     the calling thread's last error.
  *   - Packed INT4 ("canonical") layout: byte j of a row holds code k = 2j in its low nibble and
  *     code k = 2j+1 in its high nibble.
- *   - Alignment: X, Aq, meta, Wq base pointers 16-byte aligned; K % 32 == 0; ldx % 8 == 0.  Y needs
- *     only its natural 2-byte alignment and any ldy >= N.
+ *   - Alignment: X, Aq, meta, Wq, bias (b^c) and act_scale (s^a) base pointers 16-byte aligned (BASQ_EINVAL
+ *     otherwise); K % 32 == 0; ldx % 8 == 0.  Y needs only its natural 2-byte alignment and any ldy >= N.
  */
 #ifndef BASQ_H
 #define BASQ_H
@@ -158,8 +158,9 @@ int basq_group_colsums(const uint8_t* Wq, int32_t N, int32_t K, int32_t group_si
  * The fp6 operand form of an INT4 code matrix (device-side repacking; offline for weights).
  * The matrix cores of this GPU multiply 6-bit floating-point operands (e2m3: sign, 2 exponent bits,
  * 3 mantissa bits) at twice their int8 rate.  Code q in 0..15 is stored as the e2m3 number q/8, which
- * is exact; S = sum_k (qa/8)(qb/8) is exact in the fp32 accumulator for K <= 32768, and the INT32
- * accumulator of the INT4 GEMM (Sec. 5.2) is 64*S.  (The e2m3 bit pattern of q/8 is q itself.)
+ * is exact; S = sum_k (qa/8)(qb/8) is exact in the fp32 accumulator for K <= 32768 (longer rows run on the
+ * int8 path whatever operands are given), and the INT32 accumulator of the INT4 GEMM (Sec. 5.2) is 64*S.
+ * (The e2m3 bit pattern of q/8 is q itself.)
  *
  *   codes      device uint8 [rows, K/2], two codes per byte, low nibble first (as Aq and Wq)
  *   out6       out, device uint8, basq_fp6_bytes(rows, K) bytes, 16-byte aligned.  Blocks of 3072
@@ -264,6 +265,24 @@ int basq_quantize_weights(const void* W_rot, int32_t N, int32_t K, int64_t ldw,
  */
 int basq_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const void* w_scale, const void* w_zero,
                     const float* bias, const float* layer_bias, float* out_bias, void* stream);
+
+/*
+ * Everything the hot calls need from already quantised weights, in one offline call (Eq. 14: the "fused bias"
+ * W_hat b^c + b that undoes the channel bias after the product; and the weight sums that carry the activations'
+ * lower bound through the product: with x_hat = s_m q_a + z_m and W_hat = sw_n (q_w - zp_n),
+ * sum_k x_hat W_hat = s_m sw_n (ACC - zp_n rowsum_m) + z_m w_sum_n):
+ *     w_sum[n]    = fp32( double(sw_n) * (sum_k q_w[n,k] - K * zp_n) )
+ *     out_bias[n] = fp32( sum_k W_hat[n,k] * bias[k] + layer_bias[n] ),  accumulated in fp64
+ *   Wq_canonical  uint8 [N, K/2], 16-byte aligned;  w_scale, w_zero bf16 [N]
+ *   bias          fp32 [K] b^c in the rotated basis, or NULL (= 0);  layer_bias fp32 [N], or NULL (= 0)
+ *   w_sum, out_bias   out, fp32 [N] each (the w_sum and out_bias arguments of the hot calls)
+ *   Wq_prepacked  out, optional (NULL to skip): the weights in the fp6 operand form, basq_fp6_bytes(N, K) bytes,
+ *                 16-byte aligned, K % 128 == 0 -- the Wq6 argument of the hot calls (see basq_pack_fp6)
+ * Same results as basq_fused_bias and basq_pack_fp6, and the w_sum of basq_quantize_weights.
+ */
+int basq_prepare_weights(const uint8_t* Wq_canonical, int32_t N, int32_t K, const void* w_scale, const void* w_zero,
+                         const float* bias, const float* layer_bias, float* w_sum, float* out_bias,
+                         uint8_t* Wq_prepacked, void* stream);
 
 /*
  * Channel bias calibration (Sec. 3.2: the bias cancels the per-channel means after rotation):

@@ -22,7 +22,7 @@ BASQ_W_DECODE16 = 1
 STREAM_MAX_TOKENS = 128      # calls of at most this many tokens take the weight-streaming kernel (K % 128 == 0)
 
 EXPORTS = ["basq_version", "basq_last_error", "basq_rotate_quant", "basq_w4a4_gemm", "basq_workspace_bytes",
-           "basq_w4a4_gemm_grouped", "basq_group_colsums", "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_linear_fused_static", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_calibrate_bias",
+           "basq_w4a4_gemm_grouped", "basq_group_colsums", "basq_fp6_bytes", "basq_pack_fp6", "basq_decode_bytes", "basq_pack_decode", "basq_linear_fused", "basq_linear_fused_static", "basq_rotate_weights", "basq_quantize_weights", "basq_fused_bias", "basq_prepare_weights", "basq_calibrate_bias",
            "basq_hadamard28", "basq_diag_stream", "basq_diag_read", "basq_diag_mfma_i8", "basq_diag_mfma_f6"]
 
 
@@ -80,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.basq_quantize_weights.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp]
     lib.basq_fused_bias.restype = c.c_int
     lib.basq_fused_bias.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.basq_prepare_weights.restype = c.c_int
+    lib.basq_prepare_weights.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.basq_calibrate_bias.restype = c.c_int
     lib.basq_calibrate_bias.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, c.c_size_t, vp]
     lib.basq_hadamard28.restype = c.c_int
@@ -110,6 +112,12 @@ def _check(rc: int) -> None:
         raise BasqError(rc, load().basq_last_error().decode("utf-8", "replace"))
 
 
+def _need(t: Optional[torch.Tensor], nbytes: int, name: str) -> None:
+    """Raw pointers carry no size: refuse a tensor smaller than what the kernels will touch."""
+    if t is not None and t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{name} holds {t.numel() * t.element_size()} bytes, the call needs {nbytes}")
+
+
 def basq_version() -> int:
     return int(load().basq_version())
 
@@ -132,9 +140,15 @@ def basq_rotate_quant(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
                       clip_lo: float, clip_hi: float, Aq: torch.Tensor, meta: torch.Tensor,
                       rot_out: Optional[torch.Tensor] = None, *, Aq6: Optional[torch.Tensor] = None, bits: int = 4,
                       group_size: int = 0, stream: Optional[torch.cuda.Stream] = None) -> None:
-    """X bf16 [M, K] (row stride X.stride(0)); Aq uint8 [M, K/2]; meta int32 [M, 4] (16-byte records);
-    Aq6 uint8 [M, 3K/4] (optional fp6 operand form of the codes)."""
+    """X bf16 [M, K] (row stride X.stride(0)); Aq uint8 [M, K/2]; meta int32 [M * K/group_size, 4] (16-byte records,
+    one per token when group_size is 0 or K); Aq6 uint8 [basq_fp6_bytes(M, K)] = whole blocks of 32 rows (optional
+    fp6 operand form of the codes, see alloc_fp6_buffer); rot_out fp32 [M, K]."""
     M, K = X.shape
+    groups = 1 if group_size in (0, K) or group_size <= 0 else K // group_size
+    _need(Aq, M * (K // 2), "Aq")
+    _need(meta, 16 * M * groups, "meta")
+    _need(rot_out, 4 * M * K, "rot_out")
+    _need(Aq6, basq_fp6_bytes(M, K), "Aq6")
     _check(load().basq_rotate_quant(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
                                     clip_lo, clip_hi, bits, group_size, _p(Aq), _p(meta), _p(rot_out), _p(Aq6),
                                     _stream(stream)))
@@ -146,9 +160,15 @@ def basq_w4a4_gemm(Aq: torch.Tensor, meta: torch.Tensor, Wq: torch.Tensor, w_sca
                    Wq6: Optional[torch.Tensor] = None,
                    w_layout: int = BASQ_W_CANONICAL, N: Optional[int] = None,
                    stream: Optional[torch.cuda.Stream] = None) -> None:
-    """N defaults to Wq.shape[0]; give it when Wq is a flat buffer in the streaming layout."""
+    """N defaults to Wq.shape[0]; give it when Wq is a flat buffer in the streaming layout.  Aq6 / Wq6: uint8
+    [basq_fp6_bytes(M, K)] / [basq_fp6_bytes(N, K)]."""
     M, KB = Aq.shape
     N = Wq.shape[0] if N is None else N
+    _need(meta, 16 * M, "meta")
+    _need(Wq, basq_decode_bytes(N, KB * 2) if w_layout == BASQ_W_DECODE16 else N * KB, "Wq")
+    _need(Aq6, basq_fp6_bytes(M, KB * 2), "Aq6")
+    _need(Wq6, basq_fp6_bytes(N, KB * 2), "Wq6")
+    _need(acc_out, 4 * M * N, "acc_out")
     _check(load().basq_w4a4_gemm(_p(Aq), _p(meta), M, KB * 2, _p(Wq), N, w_layout, _p(w_scale), _p(w_zero),
                                  _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N, _p(acc_out),
                                  _p(Aq6), _p(Wq6), _stream(stream)))
@@ -162,6 +182,11 @@ def basq_w4a4_gemm_grouped(Aq: torch.Tensor, meta: torch.Tensor, group_size: int
     forms (both or neither)."""
     M, KB = Aq.shape
     N = Wq.shape[0]
+    if group_size > 0:
+        _need(meta, 16 * M * (KB * 2 // group_size), "meta")
+        _need(w_gsum, 4 * N * (KB * 2 // group_size), "w_gsum")
+    _need(Aq6, basq_fp6_bytes(M, KB * 2), "Aq6")
+    _need(Wq6, basq_fp6_bytes(N, KB * 2), "Wq6")
     _check(load().basq_w4a4_gemm_grouped(_p(Aq), _p(meta), M, KB * 2, group_size, _p(Wq), N, _p(w_scale), _p(w_zero),
                                          _p(w_gsum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
                                          _p(Aq6), _p(Wq6), _stream(stream)))
@@ -202,6 +227,7 @@ def basq_linear_fused(X: torch.Tensor, rot_size: int, bias: Optional[torch.Tenso
                       N: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
     M, K = X.shape
     N = Wq.shape[0] if N is None else N
+    _need(Wq6, basq_fp6_bytes(N, K), "Wq6")
     _check(load().basq_linear_fused(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias), _p(act_scale),
                                     clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout, _p(w_scale),
                                     _p(w_zero), _p(w_sum), _p(out_bias), _p(Y), Y.stride(0) if M > 0 else N,
@@ -222,6 +248,7 @@ def basq_linear_fused_static(X: torch.Tensor, rot_size: int, bias: Optional[torc
     """basq_linear_fused on the library's own workspace (no workspace argument, nothing allocated)."""
     M, K = X.shape
     N = Wq.shape[0] if N is None else N
+    _need(Wq6, basq_fp6_bytes(N, K), "Wq6")
     _check(load().basq_linear_fused_static(_p(X), M, K, X.stride(0) if M > 0 else K, rot_size, _p(bias),
                                            _p(act_scale), clip_lo, clip_hi, bits, group_size, _p(Wq), N, w_layout,
                                            _p(w_scale), _p(w_zero), _p(w_sum), _p(out_bias), _p(Y),
@@ -249,6 +276,19 @@ def basq_fused_bias(Wq: torch.Tensor, w_scale: torch.Tensor, w_zero: torch.Tenso
     N, KB = Wq.shape
     _check(load().basq_fused_bias(_p(Wq), N, KB * 2, _p(w_scale), _p(w_zero), _p(bias), _p(layer_bias),
                                   _p(out_bias), _stream(stream)))
+
+
+def basq_prepare_weights(Wq: torch.Tensor, w_scale: torch.Tensor, w_zero: torch.Tensor, bias: Optional[torch.Tensor],
+                         layer_bias: Optional[torch.Tensor], w_sum: torch.Tensor, out_bias: torch.Tensor,
+                         Wq_prepacked: Optional[torch.Tensor] = None, *,
+                         stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Wq uint8 [N, K/2] -> w_sum fp32 [N], out_bias fp32 [N], and (optional) the fp6 operand form of the weights."""
+    N, KB = Wq.shape
+    _need(w_sum, 4 * N, "w_sum")
+    _need(out_bias, 4 * N, "out_bias")
+    _need(Wq_prepacked, basq_fp6_bytes(N, KB * 2), "Wq_prepacked")
+    _check(load().basq_prepare_weights(_p(Wq), N, KB * 2, _p(w_scale), _p(w_zero), _p(bias), _p(layer_bias),
+                                       _p(w_sum), _p(out_bias), _p(Wq_prepacked), _stream(stream)))
 
 
 def basq_calibrate_bias(X: torch.Tensor, rot_size: int, act_scale: Optional[torch.Tensor], bias_out: torch.Tensor,

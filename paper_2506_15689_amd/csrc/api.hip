@@ -39,7 +39,8 @@ bool split_rot_size(int32_t n, int32_t* pow2, int32_t* has28) {
 }
 
 int validate_rotate(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, int32_t bits,
-                    int32_t group_size, float clip_lo, float clip_hi, int32_t* pow2, int32_t* has28) {
+                    int32_t group_size, float clip_lo, float clip_hi, int32_t* pow2, int32_t* has28,
+                    const float* bias = nullptr, const float* act_scale = nullptr) {
     if (M < 0) return fail(BASQ_EINVAL, "M must be >= 0 (got %lld)", (long long)M);
     if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
     if (K > 32768) return fail(BASQ_EUNSUPPORTED, "K up to 32768 is supported (got %d)", K);
@@ -54,6 +55,8 @@ int validate_rotate(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t ro
         return fail(BASQ_EINVAL, "clip ratios must be in (0, 1] (got %g, %g)", (double)clip_lo, (double)clip_hi);
     if (M > 0 && X == nullptr) return fail(BASQ_EINVAL, "X is null");
     if (!aligned16(X)) return fail(BASQ_EINVAL, "X must be 16-byte aligned");
+    // the kernels read b^c and s^a four channels at a time
+    if (!aligned16(bias) || !aligned16(act_scale)) return fail(BASQ_EINVAL, "bias and act_scale must be 16-byte aligned");
     return BASQ_OK;
 }
 
@@ -107,7 +110,7 @@ int linear_fused_impl(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
                       const uint8_t* Wq6, void* workspace,
                       size_t workspace_bytes, void* stream) {
     RotateQuantArgs a{};
-    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
+    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28, bias, act_scale);
     if (rc != BASQ_OK) return rc;
     if (group_size != 0 && group_size != K)
         return fail(BASQ_EUNSUPPORTED, "the GEMM takes per-token ranges only: group_size must be 0 or K (got %d)", group_size);
@@ -191,7 +194,7 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
                       const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
                       uint8_t* Aq, basq_tokmeta* meta, float* rot_out, uint8_t* Aq6, void* stream) {
     RotateQuantArgs a{};
-    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28);
+    int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28, bias, act_scale);
     if (rc != BASQ_OK) return rc;
     if (M > 0 && (!Aq || !meta)) return fail(BASQ_EINVAL, "Aq or meta is null");
     if (!aligned16(Aq) || !aligned16(meta) || !aligned16(rot_out) || !aligned16(Aq6))
@@ -327,13 +330,30 @@ int basq_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const void* w_scale
     if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
     if (!Wq || !w_scale || !w_zero || !out_bias) return fail(BASQ_EINVAL, "a pointer is null");
     return launch_fused_bias(Wq, N, K, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
-                             bias, layer_bias, out_bias, static_cast<hipStream_t>(stream));
+                             bias, layer_bias, out_bias, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int basq_prepare_weights(const uint8_t* Wq_canonical, int32_t N, int32_t K, const void* w_scale, const void* w_zero,
+                         const float* bias, const float* layer_bias, float* w_sum, float* out_bias,
+                         uint8_t* Wq_prepacked, void* stream) {
+    if (N <= 0) return fail(BASQ_EINVAL, "N must be >= 1 (got %d)", N);
+    if (K <= 0 || K % 32 != 0) return fail(BASQ_EINVAL, "K must be a positive multiple of 32 (got %d)", K);
+    if (!Wq_canonical || !w_scale || !w_zero || !w_sum || !out_bias) return fail(BASQ_EINVAL, "a pointer is null");
+    if (!aligned16(Wq_canonical) || !aligned16(Wq_prepacked))
+        return fail(BASQ_EINVAL, "Wq_canonical and Wq_prepacked must be 16-byte aligned");
+    if (Wq_prepacked && K % 128 != 0)
+        return fail(BASQ_EINVAL, "the fp6 operand form needs K to be a multiple of 128 (got %d)", K);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = launch_fused_bias(Wq_canonical, N, K, static_cast<const uint16_t*>(w_scale),
+                                     static_cast<const uint16_t*>(w_zero), bias, layer_bias, out_bias, w_sum, s);
+    if (rc != BASQ_OK || !Wq_prepacked) return rc;
+    return launch_pack_fp6(Wq_canonical, N, K, Wq_prepacked, s);
 }
 
 int basq_calibrate_bias(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* act_scale,
                         float* bias_out, void* workspace, size_t workspace_bytes, void* stream) {
     RotateQuantArgs a{};
-    int rc = validate_rotate(X, M, K, ldx, rot_size, 4, 0, 1.0f, 1.0f, &a.pow2, &a.has28);
+    int rc = validate_rotate(X, M, K, ldx, rot_size, 4, 0, 1.0f, 1.0f, &a.pow2, &a.has28, nullptr, act_scale);
     if (rc != BASQ_OK) return rc;
     if (M < 1) return fail(BASQ_EINVAL, "calibration needs at least one token");
     if (!bias_out || !workspace) return fail(BASQ_EINVAL, "a pointer is null");

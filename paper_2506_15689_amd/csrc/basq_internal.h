@@ -86,8 +86,9 @@ int launch_pack_fp6(const uint8_t* codes, int64_t rows, int32_t K, uint8_t* out6
 
 int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw, uint8_t* Wq,
                             uint16_t* w_scale, uint16_t* w_zero, float* w_sum, hipStream_t s);
+// out_bias and w_sum may each be null (not computed)
 int launch_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const uint16_t* w_scale, const uint16_t* w_zero,
-                      const float* bias, const float* layer_bias, float* out_bias, hipStream_t s);
+                      const float* bias, const float* layer_bias, float* out_bias, float* w_sum, hipStream_t s);
 int launch_f32_to_bf16(const float* in, uint16_t* out, int64_t count, hipStream_t s);
 int launch_column_mean(const float* r, int64_t M, int32_t K, const float* act_scale, float* out, hipStream_t s);
 

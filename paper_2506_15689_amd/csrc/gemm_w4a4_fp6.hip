@@ -381,8 +381,10 @@ double round_efficiency6(int64_t tiles, int64_t slots) {
 }  // namespace
 
 bool gemm_fp6_applicable(const GemmArgs& a) {
-    // buffer addressing: both operands must be smaller than 4 GiB
-    return a.Aq6 && a.Wq6 && a.K % 128 == 0 && a.M >= 1 &&
+    // buffer addressing: both operands must be smaller than 4 GiB.  K <= 32768: the fp32 accumulator holds the sum of
+    // K products of (q_a/8)(q_w/8) -- multiples of 1/64 up to 225 K / 64 -- exactly only while 225 K < 2^24; longer
+    // rows take the int8 path, whose INT32 accumulator has no such limit.
+    return a.Aq6 && a.Wq6 && a.K % 128 == 0 && a.K <= 32768 && a.M >= 1 &&
            (int64_t)basq_fp6_bytes(a.M, a.K) < 0xFFFFFFFFll && (int64_t)basq_fp6_bytes(a.N, a.K) < 0xFFFFFFFFll;
 }
 

@@ -64,16 +64,20 @@ __global__ __launch_bounds__(WQ_THREADS) void quantize_weights_kernel(const uint
     }
 }
 
+// out_bias[n] = sum_k W_hat[n,k] b^c[k] + layer_bias[n] (the fused bias of Eq. 14), and, when w_sum is given,
+// w_sum[n] = sw_n (sum_k q_w[n,k] - K zp_n) = sum_k W_hat[n,k] (the factor of the activations' lower bound in the
+// de-quantisation), both from the packed codes of row n.
 __global__ __launch_bounds__(WQ_THREADS) void fused_bias_kernel(const uint8_t* Wq, int N, int K, const uint16_t* w_scale,
                                                                 const uint16_t* w_zero, const float* bias,
-                                                                const float* layer_bias, float* out_bias) {
+                                                                const float* layer_bias, float* out_bias, float* w_sum) {
     __shared__ double sd[WQ_THREADS / 64];
+    __shared__ int si[WQ_THREADS / 64];
     const int n = blockIdx.x, tid = threadIdx.x;
+    const double sw = (double)bf16_to_f32(w_scale[n]);
+    const double zp = (double)bf16_to_f32(w_zero[n]);
+    const uint8_t* row = Wq + (int64_t)n * (K / 2);
     double acc = 0.0;
     if (bias) {
-        const double sw = (double)bf16_to_f32(w_scale[n]);
-        const double zp = (double)bf16_to_f32(w_zero[n]);
-        const uint8_t* row = Wq + (int64_t)n * (K / 2);
         for (int j = tid; j < K / 2; j += WQ_THREADS) {
             const int b = row[j];
             acc += sw * ((double)(b & 15) - zp) * (double)bias[2 * j];
@@ -81,7 +85,16 @@ __global__ __launch_bounds__(WQ_THREADS) void fused_bias_kernel(const uint8_t* W
         }
     }
     acc = block_reduce(acc, sd, [](double x, double y) { return x + y; });
-    if (tid == 0) out_bias[n] = (float)(acc + (layer_bias ? (double)layer_bias[n] : 0.0));
+    if (out_bias && tid == 0) out_bias[n] = (float)(acc + (layer_bias ? (double)layer_bias[n] : 0.0));
+    if (w_sum) {
+        int colsum = 0;
+        for (int j = tid; j < K / 2; j += WQ_THREADS) {
+            const int b = row[j];
+            colsum += (b & 15) + (b >> 4);
+        }
+        colsum = block_reduce(colsum, si, [](int x, int y) { return x + y; });
+        if (tid == 0) w_sum[n] = (float)(sw * ((double)colsum - (double)K * zp));
+    }
 }
 
 __global__ __launch_bounds__(WQ_THREADS) void column_mean_kernel(const float* r, int64_t M, int K, const float* act_scale,
@@ -105,9 +118,9 @@ int launch_quantize_weights(const uint16_t* W, int32_t N, int32_t K, int64_t ldw
 }
 
 int launch_fused_bias(const uint8_t* Wq, int32_t N, int32_t K, const uint16_t* w_scale, const uint16_t* w_zero,
-                      const float* bias, const float* layer_bias, float* out_bias, hipStream_t s) {
+                      const float* bias, const float* layer_bias, float* out_bias, float* w_sum, hipStream_t s) {
     hipLaunchKernelGGL(fused_bias_kernel, dim3((unsigned)N), dim3(WQ_THREADS), 0, s, Wq, N, K, w_scale, w_zero, bias,
-                       layer_bias, out_bias);
+                       layer_bias, out_bias, w_sum);
     return check_hip(hipGetLastError(), "fused_bias launch");
 }
 

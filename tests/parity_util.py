@@ -17,6 +17,7 @@ import numpy as np
 import torch
 
 import oracle
+import layout_ref
 from paper_2506_15689_amd import binding as B
 from paper_2506_15689_amd import synth_inputs as si
 
@@ -181,13 +182,13 @@ def check_fp6_path(case: Case, g: GpuResult, *, row_blocks: Optional[np.ndarray]
         got = buf.reshape(K // 128, RB, 3072)
         for rb in blocks:
             rows = codes[32 * rb:32 * rb + 32]
-            ref = oracle.pack_fp6(np.ascontiguousarray(rows)).reshape(K // 128, 1, 3072)[:, 0]
+            ref = layout_ref.pack_fp6(np.ascontiguousarray(rows)).reshape(K // 128, 1, 3072)[:, 0]
             n = rows.shape[0]
             if n == 32:
                 np.testing.assert_array_equal(got[:, rb], ref, err_msg=f"fp6 form of the {name}, row block {rb}")
             else:                                   # ragged last block: only the bytes of real rows are defined
-                mask = oracle.pack_fp6(np.full((n, K), 15, dtype=np.uint8)).reshape(K // 128, 3072) != 0
-                mask |= oracle.pack_fp6(np.full((n, K), 1, dtype=np.uint8)).reshape(K // 128, 3072) != 0
+                mask = layout_ref.pack_fp6(np.full((n, K), 15, dtype=np.uint8)).reshape(K // 128, 3072) != 0
+                mask |= layout_ref.pack_fp6(np.full((n, K), 1, dtype=np.uint8)).reshape(K // 128, 3072) != 0
                 np.testing.assert_array_equal(got[:, rb][mask], ref[mask], err_msg=f"fp6 form of the {name}, last block")
 
 
@@ -202,7 +203,7 @@ def check_decode_layout(case: Case, g: GpuResult) -> None:
     blocks = np.arange(NB) if N * K <= (1 << 22) else np.unique([0, NB // 2, NB - 1])
     canon = oracle.pack_codes(case.wq.codes)
     for nb in blocks:                               # the layout is independent per 16-row block
-        ref = oracle.pack_decode16(np.ascontiguousarray(canon[16 * nb:16 * nb + 16]))
+        ref = layout_ref.pack_decode16(np.ascontiguousarray(canon[16 * nb:16 * nb + 16]))
         np.testing.assert_array_equal(g.wd[nb * 16 * KB:(nb + 1) * 16 * KB], ref, err_msg=f"streaming layout, block {nb}")
     np.testing.assert_array_equal(g.accd, g.acc, err_msg="INT32 accumulators, streaming layout vs canonical")
     np.testing.assert_array_equal(g.yd_bits, g.y_bits, err_msg="outputs, streaming layout vs canonical")
@@ -245,3 +246,31 @@ def check_parity(case: Case, g: GpuResult, *, rows: Optional[np.ndarray] = None,
     y_i = float(np.abs(y - ref_i.y).max() / denom) if ref.y.size else 0.0
     assert y_i <= 2 ** -7, f"epilogue error {y_i} of max|ref| on identical accumulators"
     return {"flip_rate": flip_rate, "y_err": y_err, "y_err_same_acc": y_i, "rot_err": rot_err}
+
+
+def check_rows_against_oracle(X, rows, rot, bias, sa, clip_lo, clip_hi, Aq, meta, *, group=0, what=""):
+    """The rows `rows` of a finished basq_rotate_quant call (codes Aq, records meta) against the oracle's quantiser
+    on the GPU's own rotation of those rows."""
+    M, K = X.shape
+    G = K if group in (0, K) else group
+    ng = K // G
+    t_rows = torch.from_numpy(rows).to(X.device)
+    Xs = X[t_rows].contiguous()
+    r = torch.empty((len(rows), K), dtype=torch.float32, device=X.device)
+    Aq_s = torch.empty((len(rows), K // 2), dtype=torch.uint8, device=X.device)
+    meta_s = torch.empty((len(rows) * ng, 4), dtype=torch.int32, device=X.device)
+    B.basq_rotate_quant(Xs, rot, bias, sa, clip_lo, clip_hi, Aq_s, meta_s, r, group_size=group)
+    torch.cuda.synchronize()
+    ref = oracle.quantize_tokens(r.cpu().numpy(), None if bias is None else bias.cpu().numpy(),
+                                 None if sa is None else sa.cpu().numpy(), clip_lo, clip_hi, group_size=group)
+    codes = oracle.unpack_codes(Aq[t_rows].cpu().numpy())
+    mh = meta.view(M, ng, 4)[t_rows].cpu().numpy()
+    bad = np.flatnonzero((codes != ref.codes).any(axis=1))
+    assert bad.size == 0, f"{what}: codes differ from the oracle in rows {rows[bad][:8]}"
+    for name, col, want in (("scale", 0, ref.scale.view(np.uint32)), ("lower bound", 1, ref.lo.view(np.uint32)),
+                            ("row sum", 2, ref.rowsum.view(np.uint32))):
+        got = mh[:, :, col].copy().view(np.uint32)
+        bad = np.flatnonzero((got != want).any(axis=1))
+        assert bad.size == 0, (f"{what}: {name} bits differ from the oracle in rows {rows[bad][:8]}: "
+                               f"{got[bad[0]][:4]} vs {want[bad[0]][:4]}")
+    return ref

@@ -66,6 +66,8 @@ FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fa
     (dict(K=65536, ldx=65536, rot=65536), B.BASQ_EUNSUPPORTED),
     (dict(K=1056, ldx=1056, rot=32, Aq6=FAKE), B.BASQ_EINVAL),        # fp6 form needs K % 128 == 0
     (dict(Aq6=ctypes.c_void_p(0x1008)), B.BASQ_EINVAL),
+    (dict(bias=ctypes.c_void_p(0x1004)), B.BASQ_EINVAL),              # b^c and s^a are read four channels at a time
+    (dict(sa=ctypes.c_void_p(0x1008)), B.BASQ_EINVAL),
 ])
 def test_rotate_quant_rejects_bad_arguments(lib, kw, code):
     a = dict(X=FAKE, M=4, K=1024, ldx=1024, rot=1024, bias=None, sa=None, clip_lo=0.9, clip_hi=0.9, bits=4,
@@ -120,6 +122,21 @@ def test_fused_call_checks_workspace(lib):
     odd[2] = odd[3] = 1056; odd[4] = 32                                     # fp6 weights need K % 128 == 0
     odd[-1] = FAKE
     assert lib.basq_linear_fused(*odd, ctypes.c_void_p(0x2000), 1 << 20, None) == B.BASQ_EINVAL
+
+
+def test_static_workspace_call_rejects_what_does_not_fit(lib):
+    """basq_linear_fused_static: shapes whose codes and records exceed the library's own workspace fail on the
+    host, before the workspace is even looked up (so this runs without a GPU)."""
+    args = lambda M, K: [FAKE, M, K, K, K, None, None, 0.9, 0.9, 4, 0, FAKE, 256, 0, FAKE, FAKE, FAKE, None, FAKE, 256,
+                         None, None]
+    assert B.basq_workspace_bytes(4096, 8192, 256) > B.STATIC_WORKSPACE_BYTES
+    assert lib.basq_linear_fused_static(*args(4096, 8192)) == B.BASQ_EWORKSPACE
+    assert "workspace" in B.basq_last_error()
+    assert lib.basq_linear_fused_static(*args(-1, 1024)) == B.BASQ_EINVAL
+    assert lib.basq_linear_fused_static(*args(8, 1000)) == B.BASQ_EINVAL
+    header = open(os.path.join(ROOT, "include", "basq.h")).read()
+    m = re.search(r"#define\s+BASQ_STATIC_WORKSPACE_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == B.STATIC_WORKSPACE_BYTES
 
 
 def test_fp6_form_sizes_and_argument_checks(lib):
@@ -181,6 +198,14 @@ def test_offline_helpers_reject_bad_arguments(lib):
     assert lib.basq_quantize_weights(None, 8, 64, 64, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_quantize_weights(FAKE, 8, 64, 32, FAKE, FAKE, FAKE, FAKE, None) == B.BASQ_EINVAL
     assert lib.basq_fused_bias(FAKE, 0, 64, FAKE, FAKE, None, None, FAKE, None) == B.BASQ_EINVAL
+    prep = lambda **kw: lib.basq_prepare_weights(*[{**dict(Wq=FAKE, N=8, K=128, ws=FAKE, wz=FAKE, b=None, lb=None, wsum=FAKE,
+                                                           ob=FAKE, pre=None), **kw}[k]
+                                                   for k in ("Wq", "N", "K", "ws", "wz", "b", "lb", "wsum", "ob", "pre")], None)
+    assert prep(N=0) == B.BASQ_EINVAL and prep(K=48) == B.BASQ_EINVAL
+    assert prep(Wq=None) == B.BASQ_EINVAL and prep(wsum=None) == B.BASQ_EINVAL and prep(ob=None) == B.BASQ_EINVAL
+    assert prep(Wq=ctypes.c_void_p(0x1004)) == B.BASQ_EINVAL
+    assert prep(K=96, pre=FAKE) == B.BASQ_EINVAL                       # the fp6 operand form needs K % 128 == 0
+    assert prep(pre=ctypes.c_void_p(0x1008)) == B.BASQ_EINVAL
     assert lib.basq_calibrate_bias(FAKE, 16, 1024, 1024, 1024, None, FAKE, FAKE, 16 * 1024 * 4 - 1, None) == B.BASQ_EWORKSPACE
     assert lib.basq_calibrate_bias(FAKE, 0, 1024, 1024, 1024, None, FAKE, FAKE, 1 << 20, None) == B.BASQ_EINVAL
     assert lib.basq_hadamard28(None) == B.BASQ_EINVAL

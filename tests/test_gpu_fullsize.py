@@ -9,6 +9,7 @@ import pytest
 import torch
 
 import oracle
+import layout_ref
 from paper_2506_15689_amd import binding as B
 from paper_2506_15689_amd import synth_inputs as si
 
@@ -100,7 +101,7 @@ def run_fullsize(name, n_rows, n_cols, M=None):
             got = buf.view(K // 128, RB, 3072)
             for rb in sorted({0, RB // 2, R // 32 - 1}):
                 codes_rb = oracle.unpack_codes(packed[32 * rb:32 * rb + 32].cpu().numpy())
-                ref6 = oracle.pack_fp6(codes_rb).reshape(K // 128, 3072)
+                ref6 = layout_ref.pack_fp6(codes_rb).reshape(K // 128, 3072)
                 np.testing.assert_array_equal(got[:, rb].cpu().numpy(), ref6, err_msg=f"fp6 form of the {name6}, block {rb}")
         del Wq6, Aq6, Aq2, meta2, acc6, Y6, Y6f
 
@@ -122,7 +123,7 @@ def run_fullsize(name, n_rows, n_cols, M=None):
         assert torch.equal(accd, accc) and torch.equal(Yd, Yc), "streaming layout differs from canonical"
         KB, NB = K // 2, (N + 15) // 16
         for nb in sorted({0, NB // 2, NB - 1}):
-            refd = oracle.pack_decode16(Wq[16 * nb:16 * nb + 16].cpu().numpy())
+            refd = layout_ref.pack_decode16(Wq[16 * nb:16 * nb + 16].cpu().numpy())
             np.testing.assert_array_equal(Wd[nb * 16 * KB:(nb + 1) * 16 * KB].cpu().numpy(), refd,
                                           err_msg=f"streaming layout, block {nb}")
         del Wd, accc, accd, Yc, Yd

@@ -225,7 +225,7 @@ def test_ties_round_to_even_in_both_code_forms(K):
 def test_many_tokens_take_the_staged_fp6_tails(K):
     """From 32768 tokens on, the K = 4096 / 8192 kernel writes the 8-byte tail pieces of the fp6 copy through an LDS
     stage shared by the eight tokens of a workgroup.  Same bits as the plain path: codes and records of the first and
-    last thousand tokens equal those of separate short calls (which the other tests pin to the oracle), and the fp6 copy
+    last thousand tokens equal those of separate short calls, sampled tokens equal the oracle's quantiser on the GPU's rotation, and the fp6 copy
     equals the packed codes everywhere; 13 tokens past a multiple of 8 leave a ragged, odd last round, and rows past M
     in the last block stay untouched."""
     dev = "cuda"
@@ -247,6 +247,10 @@ def test_many_tokens_take_the_staged_fp6_tails(K):
         torch.cuda.synchronize()
         assert torch.equal(Aq[lo:hi], Aq_s) and torch.equal(meta[lo:hi], meta_s)
     assert int(meta[:, 2].min()) >= 0 and int(meta[:, 2].max()) <= 15 * K
+    # and straight against the oracle: 64 sampled tokens plus the first and last rounds, on the GPU's own rotation
+    rng = np.random.default_rng(K)
+    rows = np.unique(np.concatenate([rng.choice(M, 64, replace=False), np.arange(8), np.arange(M - 13, M)]))
+    pu.check_rows_against_oracle(X, rows, K, bias, None, 0.9, 0.95, Aq, meta, what="staged fp6 tails")
 
 
 def test_strided_input_and_output():
@@ -508,9 +512,9 @@ def run_grouped_layer(M, K, N, rot, *, seed=0, scale=False, odd_ldy=False):
 
 
 @pytest.mark.parametrize("M,K,N,rot", [(128, 128, 128, 128), (130, 256, 136, 128), (70, 1024, 200, 1024), (257, 512, 100, 128),
-                                       (5, 384, 17, 128), (300, 4096, 264, 4096)])
+                                       (5, 384, 17, 128), (300, 4096, 264, 4096), (200, 8192, 136, 8192), (140, 8192, 72, 128)])
 def test_grouped_gemm(M, K, N, rot):
-    """Group-wise activation ranges through the GEMM: one, two, several and 32 groups; ragged tiles in both
+    """Group-wise activation ranges through the GEMM: one, two, several, 32 and 64 groups; ragged tiles in both
     directions; output widths that are no multiple of 8; per-head rotation (128) and full rotation."""
     run_grouped_layer(M, K, N, rot, seed=M + N)
 
