@@ -6,19 +6,26 @@ then the INT4 x INT4 GEMM with fused de-quantisation -- over one batch of synthe
 that already sit in HBM.  Prints ONE JSON line:
 
   value        whole-layer throughput, 2*M*N*K integer operations per second of step time (TOPS)
-  roofline     the dominant kernel (the GEMM, int8 MFMA bound; for decode shapes HBM bound)
-  roofline_rotate_quant   the rotate+bias+quant kernel against HBM bandwidth
-  cpu_baseline the CPU oracle timed on a bounded sample of the same workload (context only)
+  roofline     the dominant kernel (the GEMM, bound by the matrix cores; for decode shapes HBM bound)
+  roofline_rotate_quant   the rotate+bias+quant kernel against HBM bandwidth, priced on the method's own bytes
+               (2.5 per channel + 16 per token); the bytes of the design's fp6 copy are reported beside it
+  other_workloads   the remaining workloads of the definition (C2, C4 prefill; C3 decode with 1, 4, 16 tokens),
+               measured in the same process after the headline one
+  cpu_baseline the CPU oracle timed on a bounded sample of the same workload, on all host threads and on one
 
-Kernel durations come from HIP events recorded on the launch stream around K back-to-back
-launches of each kernel inside the timed region.  Buffers rotate through several distinct sets so repeated steps
-do not find their inputs in the 256 MB last-level cache.
+Kernel durations come from HIP events recorded on the launch stream around back-to-back launches of
+each kernel inside the timed region (mean over all launches; minimum and median over batches of ten).
+Buffers rotate through several distinct sets so repeated steps do not find their inputs in the 256 MB
+last-level cache.  `traffic` is read from profiles/traffic.json, which the profile summariser
+(python -m paper_2506_15689_amd.profile_summary) writes from rocprofv3 counter runs of this same script.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
+import subprocess
 import sys
 import time
 
@@ -29,28 +36,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
-
-# HBM-side traffic per launch in bytes, from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised
-# under profiles/ (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE KiB, factors from a plain 256 MiB copy).
-MEASURED_TRAFFIC = {
-    ("C2", "rotate_quant"): 27564191, ("C2", "gemm"): 170037084, ("C2", "gemm_fp6"): 176944755,
-    ("C4", "rotate_quant"): 110548863, ("C4", "gemm"): 176694503, ("C4", "gemm_fp6"): 260240288,
-    ("C5", "rotate_quant"): 109842228, ("C5", "gemm"): 945431192, ("C5", "gemm_fp6"): 1294320431,
-    ("C3_M16", "rotate_quant"): 400547, ("C3_M16", "gemm"): 8984600,
-    ("C3_M1", "rotate_quant"): 39931, ("C3_M1", "gemm"): 8614970,
-}
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+OTHER_WORKLOADS = ("C2", "C4", "C3_M1", "C3_M4", "C3_M16")
 
 
-def parse_args():
+def parse_args(argv=None):
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=30)
-    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--config", default="C5",
                    help="workload name from synth_inputs.CONFIGS (default C5: the M=4096 prefill GEMM the targets are quoted on)")
     p.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through (0 = auto)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling diagnostics")
+    p.add_argument("--no-other-workloads", action="store_true",
+                   help="skip the other workloads of the definition (they run after the default C5 measurement only)")
     p.add_argument("--M", type=int, default=0, help="override the token count (sweeps)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run a plain 256 MiB device copy three times (scales the HBM byte counters of a profiler run)")
@@ -69,14 +70,17 @@ def parse_args():
                         "per-head quantiser of q, k and the KV cache")
     p.add_argument("--only", default="", choices=["", "rotate_quant"],
                    help="time only the rotate+quant kernel (large-M sweeps; value is then its GB/s)")
-    return p.parse_args()
+    p.add_argument("--no-fp6-copy", action="store_true",
+                   help="with --only rotate_quant: do not write the fp6 copy of the codes (the method's own bytes only)")
+    return p.parse_args(argv)
 
 
-def algorithmic_bytes_rotate_quant(M, K, fp6=False, group=0):
+def algorithmic_bytes_rotate_quant(M, K, fp6=False, group=0, codes4=True):
     # per token: 2K bytes of bf16 in, K/2 bytes of codes + 16 bytes per record out (one per token, or one per
-    # group), and 3K/4 bytes more when the codes are also written in the fp6 operand form
+    # group), and 3K/4 bytes more when the codes are also written in the fp6 operand form (codes4 = False: the
+    # 4-bit form is not written at all, as in the one-call layer on the fp6 path)
     records = 1 if group in (0, K) else K // group
-    return M * (2 * K + K // 2 + 16 * records + (3 * K // 4 if fp6 else 0))
+    return M * (2 * K + (K // 2 if codes4 else 0) + 16 * records + (3 * K // 4 if fp6 else 0))
 
 
 def algorithmic_bytes_gemm(M, K, N, fp6=False):
@@ -86,11 +90,33 @@ def algorithmic_bytes_gemm(M, K, N, fp6=False):
     return M * (per_code + 16) + N * per_code + N * (2 + 2 + 4 + 4) + 2 * M * N
 
 
-def cpu_baseline(cfg, lay, sample_tokens):
-    """Time the oracle (as it stands) on the first `sample_tokens` tokens x all N."""
+def load_traffic():
+    """profiles/traffic.json: {"entries": {"<workload>/<kernel>": {"bytes_per_launch": ..., ...}}, ...} or {}."""
+    try:
+        with open(TRAFFIC_JSON) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {}
+
+
+def traffic_of(table, workload, kernel):
+    """HBM-side bytes per launch of `kernel` (name prefix) on `workload` from the tracked counter summary, or None."""
+    for key, ent in table.get("entries", {}).items():
+        w, _, k = key.partition("/")
+        if w == workload and k.startswith(kernel):
+            return ent.get("bytes_per_launch")
+    return None
+
+
+# ---- CPU oracle leg (runs in a child process so that its thread count can be set; never touches the GPU) -----------
+
+def cpu_baseline_child(config, sample_tokens):
     import numpy as np
     import oracle
     from paper_2506_15689_amd import synth_inputs as si
+    cfg = si.CONFIGS[config]
+    lay = si.make_layer(cfg)
+    sample_tokens = min(sample_tokens, lay.X.shape[0])
     x = oracle.bf16_to_f32(si.bf16_bits(lay.X[:sample_tokens]))
     w = oracle.bf16_to_f32(si.bf16_bits(lay.W_rot))
     xc = oracle.bf16_to_f32(si.bf16_bits(lay.X_calib))
@@ -102,43 +128,43 @@ def cpu_baseline(cfg, lay, sample_tokens):
     res = oracle.linear(x, cfg.rot_size, bc, None, cfg.clip, cfg.clip, wq, c)
     dt = time.perf_counter() - t0
     ops = 2.0 * sample_tokens * cfg.N * cfg.K
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {sample_tokens} of {lay.X.shape[0]} tokens x all N={cfg.N}, K={cfg.K}: "
-                      f"{dt:.2f} s for rotation (fp64 dense) + quantiser + int32 triple-loop GEMM + dequant",
-            "seconds": dt, "checksum": float(np.abs(res.y).sum())}
+    print(json.dumps({"value": ops / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(), "kind": "oracle",
+                      "sample": f"first {sample_tokens} of {lay.X.shape[0]} tokens x all N={cfg.N}, K={cfg.K}: "
+                                f"{dt:.2f} s for rotation (fp64 dense) + quantiser + int32 triple-loop GEMM + dequant",
+                      "seconds": dt, "checksum": float(np.abs(res.y).sum())}))
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the layer shards over tokens or output channels without communication)",
-              file=sys.stderr)
-        sys.exit(2)
+def cpu_baseline(config, sample_tokens, threads=None):
+    """The oracle as it stands on the first `sample_tokens` tokens x all N, in a child process (threads: OpenMP and
+    BLAS thread count of the child; None = whatever the box gives it)."""
+    env = dict(os.environ)
+    if threads is not None:
+        for var in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+            env[var] = str(threads)
+    code = f"import sys; sys.path.insert(0, {ROOT!r}); import bench; bench.cpu_baseline_child({config!r}, {int(sample_tokens)})"
+    p = subprocess.run([sys.executable, "-c", code], env=env, cwd=ROOT, stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                       text=True, timeout=600)
+    lines = [l for l in p.stdout.splitlines() if l.startswith("{")]
+    if p.returncode != 0 or not lines:
+        return {"error": (p.stderr or p.stdout)[-400:]}
+    return json.loads(lines[-1])
 
+
+# ---- one workload -----------------------------------------------------------------------------------------------
+
+def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M_override=0):
+    """Prepares `config` through the library, times `steps` steps of the whole path and each kernel on its own.
+    Returns (fields of the JSON line for this workload, cfg, M)."""
     import torch
     from paper_2506_15689_amd import binding as B
     from paper_2506_15689_amd import synth_inputs as si
 
-    if args.config not in si.CONFIGS:
-        print(f"bench.py: unknown workload {args.config!r}; known: {', '.join(sorted(si.CONFIGS))}", file=sys.stderr)
-        sys.exit(2)
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    B.load()
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    cfg = si.CONFIGS[args.config]
+    cfg = si.CONFIGS[config]
     grouped = args.group_size == 128 and args.only != "rotate_quant"     # group-wise ranges through the GEMM
-    if (args.rot_size or args.group_size) and args.only != "rotate_quant" and not grouped:
-        print("bench.py: --rot-size and --group-size go with --only rotate_quant (the GEMM takes per-token ranges, "
-              "or groups of 128)", file=sys.stderr)
-        sys.exit(2)
     rot_size = args.rot_size if args.rot_size > 0 else cfg.rot_size
     group = args.group_size
-    M = args.M if args.M > 0 else cfg.M
+    M = M_override if M_override > 0 else cfg.M
     K, N = cfg.K, cfg.N
     lay = si.make_layer(cfg, M=M)
 
@@ -151,18 +177,17 @@ def main():
     cal_ws = torch.empty(Xc.shape[0] * K, dtype=torch.float32, device=dev)
     B.basq_calibrate_bias(Xc, rot_size, None, bias, cal_ws)
     out_bias = torch.empty(N, dtype=torch.float32, device=dev)
-    B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
+    rq_only = args.only == "rotate_quant"
     use_fp6 = args.matrix_path == "fp6" and K % 128 == 0 and M > B.STREAM_MAX_TOKENS and group in (0, K)
     g_fp6 = grouped and args.matrix_path == "fp6" and M > 0          # group-wise GEMM on the fp6 matrix-core path
-    want6 = use_fp6 or g_fp6
+    want6 = (use_fp6 or g_fp6) and not (rq_only and args.no_fp6_copy)
+    Wq6 = B.alloc_fp6_buffer(N, K, dev) if (use_fp6 or g_fp6) else None
+    # fused bias, weight sums and the fp6 form of the weights in the one offline call of the boundary
+    B.basq_prepare_weights(Wq, w_scale, w_zero, bias, None, w_sum, out_bias, Wq6)
     w_gsum = None
     if grouped:
         w_gsum = torch.empty((K // 128, N), dtype=torch.int32, device=dev)
         B.basq_group_colsums(Wq, 128, w_gsum)
-    Wq6 = None
-    if want6:                                # offline: the weights once more in the fp6 operand form
-        Wq6 = B.alloc_fp6_buffer(N, K, dev)
-        B.basq_pack_fp6(Wq, Wq6)
     # decode shapes stream the weights once per call: the streaming layout (offline repack), and as many
     # distinct copies as it takes to keep them out of the 256 MB last-level cache between calls
     decode = M <= B.STREAM_MAX_TOKENS and K % 128 == 0 and not grouped
@@ -180,7 +205,6 @@ def main():
         bias = None
 
     # ---- rotating buffer sets (cold-cache discipline) -------------------------------------
-    rq_only = args.only == "rotate_quant"
     per_set = M * K * 2 + M * (K // 2) + M * 16 + (0 if rq_only else M * N * 2) + (M * K * 3 // 4 if want6 else 0)
     nsets = args.sets if args.sets > 0 else max(2, min(32, -(-(640 << 20) // per_set)))
     X0 = lay.X.to(dev)
@@ -197,10 +221,16 @@ def main():
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
+    one_launch = (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192) and rot_size == K)
 
-    def rotate_quant(i):
+    # what the one-call layer launches on the fp6 path: the quantiser writes the fp6 form of the codes and leaves
+    # the 4-bit form out (nothing reads it); timed on its own in that same configuration
+    fp6_only = use_fp6 and want6 and rot_size == K and K in (4096, 8192, 14336) and group in (0, K)
+
+    def rotate_quant(i, codes4=not fp6_only):
         Xi, Aq, meta, _, Aq6 = sets[i % nsets]
-        B.basq_rotate_quant(Xi, rot_size, bias, None, cfg.clip, cfg.clip, Aq, meta, None, Aq6=Aq6, group_size=group, stream=stream)
+        B.basq_rotate_quant(Xi, rot_size, bias, None, cfg.clip, cfg.clip, Aq if codes4 else None, meta, None, Aq6=Aq6,
+                            group_size=group, stream=stream)
 
     def gemm(i):
         _, Aq, meta, Y, Aq6 = sets[i % nsets]
@@ -225,33 +255,44 @@ def main():
         B.basq_linear_fused(Xi, cfg.rot_size, bias, None, cfg.clip, cfg.clip, wsets[i % len(wsets)], w_scale, w_zero,
                             w_sum, out_bias, Y, workspace, Wq6=Wq6, w_layout=w_layout, N=N, stream=stream)
 
-    def timed(fn, count):
-        """`count` back-to-back calls bracketed by two events on the launch stream; ms per call."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def timed(fn, count, batch=10):
+        """`count` back-to-back calls on the launch stream.  Events bracket the whole run (-> mean) and sit between
+        batches of `batch` calls (-> minimum and median of the batch means).  Times in ms per call."""
+        nb = max(1, count // batch)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(nb + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        e0.record(stream)
-        for i in range(count):
-            fn(i)
-        e1.record(stream)
+        marks[0].record(stream)
+        done, calls = 0, []
+        for b in range(nb):
+            upto = count if b == nb - 1 else (b + 1) * batch
+            for i in range(done, upto):
+                fn(i)
+            marks[b + 1].record(stream)
+            calls.append(upto - done)
+            done = upto
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / count
-        return e0.elapsed_time(e1) / count, wall_ms
+        per_batch = [marks[b].elapsed_time(marks[b + 1]) / calls[b] for b in range(nb)]
+        return {"mean": marks[0].elapsed_time(marks[nb]) / count, "min": min(per_batch),
+                "median": statistics.median(per_batch), "wall": wall_ms, "launches": count}
 
     whole = rotate_quant if rq_only else step
-    for i in range(nsets):                      # every set holds valid codes before anything is timed
-        rotate_quant(i)
-    for i in range(args.warmup):
+    for i in range(nsets):                      # every set holds valid codes (both forms) before anything is timed
+        rotate_quant(i, True)
+    for i in range(warmup):
         whole(i)
         rotate_quant(i)
         if not rq_only:
             gemm(i)
     torch.cuda.synchronize()
 
-    # the timed region: K steps of the whole path, then K launches of each kernel on its own so
-    # that each kernel's average duration is known (events around every single launch would add
-    # several microseconds of their own to kernels this short)
-    _, ms_step = timed(whole, args.steps)
+    # the timed region: K steps of the whole path, then launches of each kernel on its own so that each kernel's
+    # average duration is known (events around every single launch would add several microseconds of their own
+    # to kernels this short)
+    t_step = timed(whole, steps)
+    ms_step = t_step["mean"]
+    graph_note = None
     if args.graph:
         # the same K steps, recorded once on a capture stream and replayed: the device-side time of the step
         cap = torch.cuda.Stream()
@@ -260,7 +301,7 @@ def main():
         eager_stream = stream
         with torch.cuda.graph(g, stream=cap):
             stream = torch.cuda.current_stream()
-            for i in range(args.steps):
+            for i in range(steps):
                 whole(i)
         stream = eager_stream
         torch.cuda.synchronize()
@@ -271,15 +312,20 @@ def main():
         g.replay()
         e1.record(stream)
         torch.cuda.synchronize()
-        ms_step_eager, ms_step = ms_step, e0.elapsed_time(e1) / args.steps
-    rq_ms, _ = timed(rotate_quant, args.steps)
-    gemm_ms = float("nan") if rq_only else timed(gemm, args.steps)[0]
-    gemm_int8_ms = timed(gemm_int8, args.steps)[0] if use_fp6 and not rq_only else None
+        graph_note = {"eager_ms_per_step": ms_step}
+        ms_step = e0.elapsed_time(e1) / steps
+    launches = max(steps, 50) if steps >= 10 else steps
+    t_rq = timed(rotate_quant, launches)
+    t_gemm = None if rq_only else timed(gemm, launches)
+    t_gemm8 = timed(gemm_int8, launches) if use_fp6 and not rq_only else None
+    rq_ms = t_rq["mean"]
+    gemm_ms = float("nan") if rq_only else t_gemm["mean"]
     ops = 0.0 if rq_only else 2.0 * M * N * K
     value = ops / (ms_step * 1e-3) / 1e12
 
-    if args.M > 0 or args.no_bias or args.rot_size or args.group_size or (args.matrix_path == "int8" and M > B.STREAM_MAX_TOKENS):
-        MEASURED_TRAFFIC.clear()                  # the stored counters belong to the unmodified configurations
+    modified = bool(M_override > 0 or args.no_bias or args.rot_size or args.group_size or
+                    (args.matrix_path == "int8" and M > B.STREAM_MAX_TOKENS) or args.no_fp6_copy)
+    table = {} if modified else traffic_table     # the stored counters belong to the unmodified configurations
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -290,7 +336,7 @@ def main():
 
     # ---- measured ceilings of this machine (diagnostic kernels of the library; a few milliseconds) ------
     ceilings = {}
-    if not args.no_ceilings:
+    if with_ceilings:
         ct = max(M, 32768)                                  # enough tokens to reach the streaming asymptote
         ck = (K + 2047) // 2048 * 2048                      # the streaming kernel moves whole 2048-channel pieces
         csrc = torch.empty(ct * 2 * ck, dtype=torch.uint8, device=dev).fill_(1)
@@ -301,7 +347,7 @@ def main():
             B.basq_diag_stream(csrc, cdst, cmeta, ct, ck, stream=stream)
         for i in range(3):
             stream_once(i)
-        ms, _ = timed(stream_once, 10)
+        ms = timed(stream_once, 10)["mean"]
         ceilings["hbm_stream_GBps"] = ct * (2 * ck + ck // 2 + 16) / (ms * 1e-3) / 1e9
         del csrc, cdst, cmeta
         cout = torch.empty(512 * 256, dtype=torch.int32, device=dev)
@@ -310,7 +356,7 @@ def main():
         def mfma_once(i):
             B.basq_diag_mfma_i8(cout, 512, iters, stream=stream)
         mfma_once(0)
-        ms, _ = timed(mfma_once, 3)
+        ms = timed(mfma_once, 3)["mean"]
         ceilings["int8_mfma_TOPS"] = 512 * 4 * 8 * iters * 65536.0 / (ms * 1e-3) / 1e12
         del cout
         fout = torch.empty(512 * 256, dtype=torch.float32, device=dev)
@@ -318,90 +364,181 @@ def main():
         def mfma6_once(i):
             B.basq_diag_mfma_f6(fout, 512, iters, stream=stream)
         mfma6_once(0)
-        ms, _ = timed(mfma6_once, 3)
+        ms = timed(mfma6_once, 3)["mean"]
         ceilings["fp6_mfma_TOPS"] = 512 * 4 * 8 * iters * 131072.0 / (ms * 1e-3) / 1e12
         del fout
-        if decode and not rq_only:
-            # read-only streaming over the same weight copies, launched the same way as the decode kernel
-            views = [w.view(-1)[: w.numel() // 32768 * 32768] for w in wsets]
-            rout = torch.empty(1024 * 256, dtype=torch.int32, device=dev)
+    if decode and not rq_only:
+        # read-only streaming over the same weight copies, launched the same way as the decode kernel: what a
+        # kernel that only reads these bytes achieves at this size (a launch of a few microseconds is latency)
+        views = [w.view(-1)[: w.numel() // 32768 * 32768] for w in wsets]
+        rout = torch.empty(1024 * 256, dtype=torch.int32, device=dev)
 
-            def read_once(i):
-                B.basq_diag_read(views[i % len(views)], rout, 1024, stream=stream)
-            if views[0].numel() > 0:
-                for i in range(3):
-                    read_once(i)
-                ms, _ = timed(read_once, 20)
-                ceilings["hbm_read_GBps"] = views[0].numel() / (ms * 1e-3) / 1e9
-            del rout
+        def read_once(i):
+            B.basq_diag_read(views[i % len(views)], rout, 1024, stream=stream)
+        if views[0].numel() > 0:
+            for i in range(3):
+                read_once(i)
+            t_read = timed(read_once, launches)
+            ceilings["hbm_read_GBps"] = views[0].numel() / (t_read["mean"] * 1e-3) / 1e9
+            ceilings["hbm_read_us"] = t_read["mean"] * 1e3
+        del rout
 
-    rq_bytes = algorithmic_bytes_rotate_quant(M, K, want6, group)
+    def spread(t):
+        return {"avg_kernel_ms": t["mean"], "min_kernel_ms": t["min"], "median_kernel_ms": t["median"], "launches": t["launches"]}
+
+    # rotate+quant: priced on the method's own bytes (bf16 in, 4-bit codes and one record out); what this design
+    # moves on top (the fp6 copy of the codes that its GEMM reads) is reported, not credited
+    rq_bytes = algorithmic_bytes_rotate_quant(M, K, False, group)
+    rq_design = algorithmic_bytes_rotate_quant(M, K, want6, group, codes4=not fp6_only)
     gemm_bytes = algorithmic_bytes_gemm(M, K, N, use_fp6)
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
+    rq_kernel = ("rotate_quant_k28_kernel" if (K == 14336 and rot_size == K and group in (0, K)) else
+                 "rotate_quant_pow2" if (K in (4096, 8192) and rot_size == K and group in (0, K, 128)) else
+                 "rotate_quant_head_kernel" if (rot_size == 128 and group == 128 and K % 512 == 0) else "rotate_quant_generic_kernel")
+    rq_traffic = traffic_of(table, config, rq_kernel)
+    roof_rq = {"kernel": rq_kernel, "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+               "frac": rq_gbs / HBM_PEAK_GBS, "traffic": rq_traffic, "algorithmic_bytes": rq_bytes,
+               "writes_4bit_codes": not fp6_only, "design_bytes": rq_design, "achieved_on_design_bytes": rq_design / (rq_ms * 1e-3) / 1e9,
+               "traffic_over_algorithmic": (rq_traffic / rq_bytes) if rq_traffic else None, **spread(t_rq)}
     if rq_only:
         roof = None
     elif decode:
         ach = gemm_bytes / (gemm_ms * 1e-3) / 1e9
         roof = {"kernel": "gemv_w4a4_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "gemm")),
-                "algorithmic_bytes": gemm_bytes, "avg_kernel_ms": gemm_ms}
+                "frac": ach / HBM_PEAK_GBS, "traffic": traffic_of(table, config, "gemv_w4a4_kernel"),
+                "algorithmic_bytes": gemm_bytes, **spread(t_gemm)}
+        # the whole step as one HBM-bound pass: activations in, weights once, outputs out
+        step_bytes = gemm_bytes - M * (K // 2 + 16) + 2 * M * K
+        roof["step_algorithmic_bytes"] = step_bytes
+        roof["step_GBps"] = step_bytes / (ms_step * 1e-3) / 1e9
+        roof["step_frac"] = roof["step_GBps"] / HBM_PEAK_GBS
     else:
         ach = ops / (gemm_ms * 1e-3) / 1e12
-        peak = FP6_PEAK_TOPS if want6 else INT8_PEAK_TOPS
-        tkey = "gemm_fp6" if use_fp6 else "gemm"
-        roof = {"kernel": "gemm_w4a4_fp6_kernel" if use_fp6 else (("gemm_w4a4_grouped_fp6_kernel" if g_fp6 else "gemm_w4a4_grouped_kernel") if grouped else "gemm_w4a4_direct_kernel"),
-                "bound": "mfma",
-                "achieved": ach, "peak": peak, "unit": "TOP/s", "frac": ach / peak,
-                "traffic": MEASURED_TRAFFIC.get((args.config, tkey)), "algorithmic_ops": ops, "avg_kernel_ms": gemm_ms}
+        peak = FP6_PEAK_TOPS if (use_fp6 or g_fp6) else INT8_PEAK_TOPS
+        kname = ("gemm_w4a4_fp6_kernel" if use_fp6 else
+                 (("gemm_w4a4_grouped_fp6_kernel" if g_fp6 else "gemm_w4a4_grouped_kernel") if grouped else "gemm_w4a4_direct_kernel"))
+        roof = {"kernel": kname, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TOP/s", "frac": ach / peak,
+                "traffic": traffic_of(table, config, kname), "algorithmic_ops": ops, "algorithmic_bytes": gemm_bytes,
+                **spread(t_gemm)}
+        if roof["traffic"]:
+            roof["traffic_over_algorithmic"] = roof["traffic"] / gemm_bytes
         if use_fp6:
-            # the same product on the int8 matrix-core path (bit-identical output), for comparison
-            ach8 = ops / (gemm_int8_ms * 1e-3) / 1e12
+            # the same product on the int8 matrix-core path (bit-identical output): the pipe the workload
+            # definition prices the GEMM against
+            ach8 = ops / (t_gemm8["mean"] * 1e-3) / 1e12
             roof["frac_of_int8_peak"] = ach / INT8_PEAK_TOPS
             roof["int8_path"] = {"kernel": "gemm_w4a4_direct_kernel", "achieved": ach8, "peak": INT8_PEAK_TOPS,
-                                 "frac": ach8 / INT8_PEAK_TOPS, "avg_kernel_ms": gemm_int8_ms,
-                                 "traffic": MEASURED_TRAFFIC.get((args.config, "gemm"))}
-    roof_rq = {"kernel": "rotate_quant", "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-               "frac": rq_gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, "rotate_quant")),
-               "algorithmic_bytes": rq_bytes, "avg_kernel_ms": rq_ms}
+                                 "frac": ach8 / INT8_PEAK_TOPS, "traffic": traffic_of(table, config, "gemm_w4a4_direct_kernel"),
+                                 **spread(t_gemm8)}
 
-    if ceilings:
+    if "hbm_stream_GBps" in ceilings:
         roof_rq["measured_ceiling"] = ceilings["hbm_stream_GBps"]
         roof_rq["frac_of_measured_ceiling"] = rq_gbs / ceilings["hbm_stream_GBps"]
-        if roof is not None and roof["bound"] == "mfma":
-            ckey = "fp6_mfma_TOPS" if use_fp6 else "int8_mfma_TOPS"
-            roof["measured_ceiling"] = ceilings[ckey]
-            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings[ckey]
-            if use_fp6:
-                roof["int8_path"]["measured_ceiling"] = ceilings["int8_mfma_TOPS"]
-        elif roof is not None:
-            ckey = "hbm_read_GBps" if "hbm_read_GBps" in ceilings else "hbm_stream_GBps"
-            roof["measured_ceiling"] = ceilings[ckey]
-            roof["measured_ceiling_kind"] = ("read-only stream over the same weight buffers, same launch path"
-                                             if ckey == "hbm_read_GBps" else "read+write stream")
-            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings[ckey]
+    if roof is not None and roof["bound"] == "mfma" and "fp6_mfma_TOPS" in ceilings:
+        ckey = "fp6_mfma_TOPS" if (use_fp6 or g_fp6) else "int8_mfma_TOPS"
+        roof["measured_ceiling"] = ceilings[ckey]
+        roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings[ckey]
+        if use_fp6:
+            roof["int8_path"]["measured_ceiling"] = ceilings["int8_mfma_TOPS"]
+    elif roof is not None and "hbm_read_GBps" in ceilings:
+        roof["measured_ceiling"] = ceilings["hbm_read_GBps"]
+        roof["measured_ceiling_kind"] = ("read-only kernel over the same weight buffers, same launch path: "
+                                         f"{ceilings['hbm_read_us']:.2f} us per launch (a launch this small is latency, not bandwidth)")
+        roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["hbm_read_GBps"]
 
     out = {
-        "metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
-        "value": rq_gbs if rq_only else value, "unit": "GB/s" if rq_only else "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if want6 and not rq_only
+        "value": rq_gbs if rq_only else value, "unit": "GB/s" if rq_only else "TOPS",
+        "ms_per_step": ms_step, "min_ms_per_step": t_step["min"], "median_ms_per_step": t_step["median"],
+        "dtype": ("int4 codes as exact fp6 (e2m3) operands -> f32 accumulator == int32 (f8f6f4 MFMA)" if (use_fp6 or g_fp6) and not rq_only
                   else "int4 x int4 -> int32 (int8 MFMA)") + "; rotation and quantiser in f32; bf16 in/out",
-        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.description}", "M": M, "K": K, "N": N, "rot_size": rot_size, "group_size": group if group else K,
                    "clip": cfg.clip, "buffer_sets": nsets, "weight_copies": len(wsets),
                    "weight_layout": "streaming (16-row blocks)" if w_layout == B.BASQ_W_DECODE16 else "canonical",
                    "launch": "HIP graph replay of the K steps" if args.graph else "eager",
-                   "step_launches": 1 if (w_layout == B.BASQ_W_DECODE16 and M <= 4 and N <= 4096 and K in (4096, 8192)
-                                          and rot_size == K) else 2,
-                   "matrix_path": "fp6" if want6 else ("int4 weight streaming" if decode else "int8")},
+                   "step_launches": 1 if one_launch else 2,
+                   "matrix_path": "fp6" if (use_fp6 or g_fp6) else ("int4 weight streaming" if decode else "int8")},
         "rotate_quant_GBps": rq_gbs,
         "roofline": roof_rq if rq_only else roof,
         "roofline_rotate_quant": roof_rq,
     }
-    if not args.no_cpu_baseline and not rq_only and not grouped:
-        # about 1.5e12 integer operations keep the oracle busy for 10-30 s on the box's 16 host cores
-        sample = max(1, min(M, int(round(1.5e12 / (2.0 * N * K)))))
-        out["cpu_baseline"] = cpu_baseline(cfg, lay, sample)
+    if graph_note:
+        out["graph"] = graph_note
+    del sets, workspace, wsets, Wq, Wq6, X0
+    torch.cuda.empty_cache()
+    return out, cfg, M
+
+
+def compact(full):
+    """The few numbers of a secondary workload that go into the headline line."""
+    r, q = full["roofline"], full["roofline_rotate_quant"]
+    c = {"M": full["config"]["M"], "K": full["config"]["K"], "N": full["config"]["N"], "matrix_path": full["config"]["matrix_path"],
+         "step_launches": full["config"]["step_launches"], "ms_per_step": full["ms_per_step"], "TOPS": full["value"],
+         "dominant": {k: r.get(k) for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "avg_kernel_ms",
+                                            "min_kernel_ms", "median_kernel_ms", "frac_of_int8_peak", "measured_ceiling",
+                                            "frac_of_measured_ceiling", "step_GBps", "step_frac") if r.get(k) is not None},
+         "rotate_quant": {k: q.get(k) for k in ("kernel", "achieved", "frac", "algorithmic_bytes", "design_bytes", "traffic",
+                                                "avg_kernel_ms", "min_kernel_ms", "median_kernel_ms") if q.get(k) is not None}}
+    if "int8_path" in r:
+        c["dominant"]["int8_path_frac_of_int8_peak"] = r["int8_path"]["frac"]
+    return c
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the layer shards over tokens or output channels without communication)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_15689_amd import binding as B
+    from paper_2506_15689_amd import synth_inputs as si
+
+    if args.config not in si.CONFIGS:
+        print(f"bench.py: unknown workload {args.config!r}; known: {', '.join(sorted(si.CONFIGS))}", file=sys.stderr)
+        sys.exit(2)
+    grouped = args.group_size == 128 and args.only != "rotate_quant"
+    if (args.rot_size or args.group_size) and args.only != "rotate_quant" and not grouped:
+        print("bench.py: --rot-size and --group-size go with --only rotate_quant (the GEMM takes per-token ranges, "
+              "or groups of 128)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load()
+    torch.cuda.set_device(torch.device("cuda:0"))
+    table = load_traffic()
+
+    main_fields, cfg, M = run_workload(args, args.config, args.steps, args.warmup, with_ceilings=not args.no_ceilings,
+                                       traffic_table=table, M_override=args.M)
+    out = {"metric": "W4A4 rotated-linear TOPS + fused rotate/quant GB/s, % of roofline, 1 MI355X",
+           "value": main_fields.pop("value"), "unit": main_fields.pop("unit"), "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": main_fields.pop("ms_per_step"), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": main_fields.pop("dtype"), "data": "synthetic"}
+    out.update(main_fields)
+    if table.get("source"):
+        out["traffic_source"] = table["source"]
+
+    plain = (args.config == "C5" and not args.only and not args.M and not args.group_size and not args.rot_size and
+             not args.no_bias and not args.graph and args.matrix_path == "fp6" and args.weight_layout == "stream")
+    if plain and not args.no_other_workloads:
+        others = {}
+        for name in OTHER_WORKLOADS:
+            full, _, _ = run_workload(args, name, max(10, min(args.steps, 50)), max(5, min(args.warmup, 10)),
+                                      with_ceilings=False, traffic_table=table)
+            others[name] = compact(full)
+        out["other_workloads"] = others
+
+    if not args.no_cpu_baseline and not args.only and not grouped:
+        # about 1.5e12 integer operations keep the oracle busy for 10-30 s on the box's host threads; one thread
+        # gets a twelfth of the sample
+        sample = max(1, min(M, int(round(1.5e12 / (2.0 * cfg.N * cfg.K)))))
+        base = cpu_baseline(args.config, sample)
+        if "error" not in base:
+            one = cpu_baseline(args.config, max(1, sample // 12), threads=1)
+            base["single_thread"] = one
+        out["cpu_baseline"] = base
     print(json.dumps(out))
 
 

@@ -84,7 +84,9 @@ const char* basq_last_error(void);
  *              the KV cache with rot_size = group_size = head_dim; Sec. 5 "Deployment Details").  Such
  *              codes are not an input of basq_w4a4_gemm; with group_size = 128 they are the input of
  *              basq_w4a4_gemm_grouped.
- *   Aq         out, uint8 [M, K/2] canonical packed codes
+ *   Aq         out, uint8 [M, K/2] canonical packed codes.  May be NULL when Aq6 is given, with per-token ranges and
+ *              rot_size == K in {4096, 8192, 14336} (the quantiser writes the fp6 form itself and then leaves the
+ *              4-bit form out; elsewhere BASQ_EUNSUPPORTED)
  *   meta       out, [M, K/group_size] records, token-major (group_size 0 counts as K)
  *   rot_out    out, optional debug dump of r, fp32 [M, K]; NULL to skip
  *   Aq6        out, optional (NULL to skip): the same codes in the fp6 operand form described at

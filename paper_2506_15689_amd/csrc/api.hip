@@ -102,6 +102,13 @@ int validate_fp6(const uint8_t* Aq6, const uint8_t* Wq6, bool need_a, int32_t K)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// The kernels that write the fp6 form of the codes themselves can leave the 4-bit form out.
+bool fp6_only_applicable(const RotateQuantArgs& a) {
+    RotateQuantArgs b = a;
+    b.Aq = nullptr;
+    return b.Aq6 != nullptr && b.group == b.K && (rotate_quant_pow2_applicable(b) || rotate_quant_k28_applicable(b));
+}
+
 // the one-call layer on a workspace of the caller's or of the library's own (both entry points end here)
 int linear_fused_impl(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t rot_size, const float* bias,
                       const float* act_scale, float clip_lo, float clip_hi, int32_t bits, int32_t group_size,
@@ -141,6 +148,9 @@ int linear_fused_impl(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmArgs g{Aq, meta, M, K, Wq, N, static_cast<const uint16_t*>(w_scale), static_cast<const uint16_t*>(w_zero),
                w_sum, out_bias, static_cast<uint16_t*>(Y), ldy, nullptr, Aq6, Aq6 ? Wq6 : nullptr, w_layout};
+    // when the product runs on the fp6 matrix path nothing reads the 4-bit codes: where the quantiser writes the
+    // fp6 form itself it leaves them out
+    if (Aq6 && gemm_fp6_applicable(g) && fp6_only_applicable(a)) a.Aq = nullptr;
     if (w_layout != BASQ_W_CANONICAL && M > GEMV_MAX_TOKENS && !gemm_fp6_applicable(g))      // before anything is launched
         return fail(BASQ_EUNSUPPORTED, "more than 128 tokens with the streaming weight layout need the fp6 operands "
                                         "(the int8 kernels read canonical weights)");
@@ -196,7 +206,7 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     RotateQuantArgs a{};
     int rc = validate_rotate(X, M, K, ldx, rot_size, bits, group_size, clip_lo, clip_hi, &a.pow2, &a.has28, bias, act_scale);
     if (rc != BASQ_OK) return rc;
-    if (M > 0 && (!Aq || !meta)) return fail(BASQ_EINVAL, "Aq or meta is null");
+    if (M > 0 && (!(Aq || Aq6) || !meta)) return fail(BASQ_EINVAL, "Aq or meta is null");
     if (!aligned16(Aq) || !aligned16(meta) || !aligned16(rot_out) || !aligned16(Aq6))
         return fail(BASQ_EINVAL, "Aq, meta, rot_out and Aq6 must be 16-byte aligned");
     if (Aq6 && K % 128 != 0) return fail(BASQ_EINVAL, "the fp6 operand form needs K %% 128 == 0 (got %d)", K);
@@ -205,6 +215,9 @@ int basq_rotate_quant(const void* X, int64_t M, int32_t K, int64_t ldx, int32_t 
     a.bias = bias; a.act_scale = act_scale; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
     a.group = group_size == 0 ? K : group_size;
     a.Aq = Aq; a.meta = meta; a.rot_out = rot_out; a.Aq6 = Aq6;
+    if (M > 0 && !Aq && !fp6_only_applicable(a))
+        return fail(BASQ_EUNSUPPORTED, "Aq may be NULL only where the quantiser writes the fp6 form itself: per-token ranges "
+                                        "with rot_size == K in {4096, 8192, 14336}");
     return launch_rotate_quant(a, static_cast<hipStream_t>(stream));
 }
 

@@ -324,20 +324,23 @@ __global__ __launch_bounds__(K28_WAVES * 64, 8 / K28_WAVES) void rotate_quant_k2
         // A lane holds 64 consecutive output bytes as four 16-byte pieces.  Transposing the pieces over
         // (jb, g) lets every store instruction write whole 64-byte segments (piece jb of lane g goes to
         // register g of lane jb), instead of four partial writes per segment.
+        // (The 4-bit form is optional when the fp6 form is written.)
+        if (a.Aq) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            auto s0 = __builtin_amdgcn_permlane16_swap(words[0][r], words[1][r], false, false);
-            auto s1 = __builtin_amdgcn_permlane16_swap(words[2][r], words[3][r], false, false);
-            auto t0 = __builtin_amdgcn_permlane32_swap(s0[0], s1[0], false, false);
-            auto t1 = __builtin_amdgcn_permlane32_swap(s0[1], s1[1], false, false);
-            words[0][r] = t0[0]; words[2][r] = t0[1];
-            words[1][r] = t1[0]; words[3][r] = t1[1];
-        }
-        if (row_valid && tok_valid) {
-            uint8_t* orow = a.Aq + m * (int64_t)(K28 / 2) + ip * 256 + 16 * g;
+            for (int r = 0; r < 4; ++r) {
+                auto s0 = __builtin_amdgcn_permlane16_swap(words[0][r], words[1][r], false, false);
+                auto s1 = __builtin_amdgcn_permlane16_swap(words[2][r], words[3][r], false, false);
+                auto t0 = __builtin_amdgcn_permlane32_swap(s0[0], s1[0], false, false);
+                auto t1 = __builtin_amdgcn_permlane32_swap(s0[1], s1[1], false, false);
+                words[0][r] = t0[0]; words[2][r] = t0[1];
+                words[1][r] = t1[0]; words[3][r] = t1[1];
+            }
+            if (row_valid && tok_valid) {
+                uint8_t* orow = a.Aq + m * (int64_t)(K28 / 2) + ip * 256 + 16 * g;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                nt_store16(orow + 64 * j, make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]));
+                for (int j = 0; j < 4; ++j)
+                    nt_store16(orow + 64 * j, make_uint4(words[j][0], words[j][1], words[j][2], words[j][3]));
+            }
         }
         sum += dppi<0xB1>(sum);
         sum += dppi<0x4E>(sum);
@@ -378,7 +381,8 @@ int launch_k28_flags(const RotateQuantArgs& a, hipStream_t s, float norm, const 
 }  // namespace
 
 bool rotate_quant_k28_applicable(const RotateQuantArgs& a) {
-    return a.group == a.K && a.has28 && a.rot_size == K28 && a.K == K28 && a.Aq != nullptr && a.meta != nullptr;
+    return a.group == a.K && a.has28 && a.rot_size == K28 && a.K == K28 && (a.Aq != nullptr || a.Aq6 != nullptr) &&
+           a.meta != nullptr;
 }
 
 int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s) {

@@ -55,7 +55,8 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
     };
 
     // K = 4096: the first token is requested before the bias is staged, so that the two latencies overlap
-    // (K = 8192 has no registers to carry a token across the loop edge)
+    // (K = 8192 has no registers to carry a token across the loop edge: even a first token requested here keeps its
+    // 64 registers live around the loop and the kernel spills)
     int64_t m = wave_id;
     if (PREFETCH && m < a.M) load_token(m);
     if (HAS_BIAS) {
@@ -75,8 +76,9 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
             // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
             [&]() { if (PREFETCH && mnext < a.M) load_token(mnext); },
             [&](int hf, int b, const uint32_t (&words)[4], const v16f& te, const v16f& to) {
-                uint8_t* dst = a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane;
-                nt_store16(dst, make_uint4(words[0], words[1], words[2], words[3]));
+                // the 4-bit form is optional when the fp6 form is written (the one-call layer on the fp6 path reads only that)
+                if (a.Aq) nt_store16(a.Aq + m * (int64_t)(K / 2) + 2048 * hf + 1024 * b + 16 * lane,
+                                     make_uint4(words[0], words[1], words[2], words[3]));
                 if (a.Aq6) {
                     // The same 32 codes as e2m3 numbers q/8, straight from the clamped values t in [0, 15]: the
                     // packed conversion divides by its scale operand, rounds to nearest-even -- on the e2m3 grid
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuan
         active, part, raw4, bop, tr + wave * P2_LDS_WORDS, xch + tl * (NWAY * 512), lred + tl * (NWAY * 2),
         reinterpret_cast<const float4*>(lbias_s), a.act_scale, norm, a.clip_lo, a.clip_hi, lane,
         pl.wbase, pl.rbase, [&](const uint32_t (&words)[4], const v16f& te, const v16f& to) {
-            nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * part + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
+            if (a.Aq) nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * part + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
             if (a.Aq6) {      // the fp6 copy, as in the one-wave kernel: group 64*part + lane of the token
                 const v6i f6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(te, to, 8.0f);
                 const int g = 64 * part + lane, f = g & 3, r = (int)(m & 31);
@@ -229,8 +231,9 @@ int launch_nc(const RotateQuantArgs& a, hipStream_t s, float norm) {
 
 bool rotate_quant_pow2_applicable(const RotateQuantArgs& a) {
     // per-token ranges, or groups of 128 channels (four neighbouring lanes; no fp6 copy: the GEMM that takes it is per token)
+    // (the 4-bit codes may be left out when the fp6 form is written)
     return (a.group == a.K || (a.group == 128 && a.Aq6 == nullptr)) && !a.has28 && a.rot_size == a.K &&
-           (a.K == 4096 || a.K == 8192) && a.Aq != nullptr && a.meta != nullptr;
+           (a.K == 4096 || a.K == 8192) && (a.Aq != nullptr || a.Aq6 != nullptr) && a.meta != nullptr;
 }
 
 int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s) {

@@ -62,6 +62,8 @@ FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fa
     (dict(X=None), B.BASQ_EINVAL),
     (dict(X=ctypes.c_void_p(0x1008)), B.BASQ_EINVAL),
     (dict(Aq=None), B.BASQ_EINVAL),
+    (dict(Aq=None, Aq6=FAKE), B.BASQ_EUNSUPPORTED),                   # the fp6 form alone: only where the quantiser writes it itself
+    (dict(Aq=None, Aq6=FAKE, K=4096, ldx=4096, rot=4096, group=128), B.BASQ_EUNSUPPORTED),
     (dict(meta=None), B.BASQ_EINVAL),
     (dict(K=65536, ldx=65536, rot=65536), B.BASQ_EUNSUPPORTED),
     (dict(K=1056, ldx=1056, rot=32, Aq6=FAKE), B.BASQ_EINVAL),        # fp6 form needs K % 128 == 0

@@ -132,6 +132,15 @@ def test_degenerate_tokens_on_the_fast_kernels(K, M, with_bias, with_scale):
     pu.check_rows_against_oracle(X, rows, K, bias, sa, clip_lo, clip_hi, Aq2, meta2, what="with the fp6 copy")
     assert torch.equal(Aq2, Aq) and torch.equal(meta2[:, :3], meta[:, :3]), "codes or records change with the fp6 copy"
     check_fp6_copy(Aq2, A6, K, sorted({f // 32 for f in specials} | {(M - 1) // 32 - 1}))
+    # the fp6 form alone (what the one-call layer asks for on the fp6 matrix path): same records, same fp6 bytes
+    meta3 = torch.full_like(meta2, -7)
+    A6c = B.alloc_fp6_buffer(M, K, DEV).zero_()
+    B.basq_rotate_quant(X, K, bias, sa, clip_lo, clip_hi, None, meta3, Aq6=A6c)
+    torch.cuda.synchronize()
+    full = M // 32
+    assert torch.equal(meta3[:, :3], meta2[:, :3]), "records change when the 4-bit codes are left out"
+    assert torch.equal(A6c.view(K // 128, -1, 3072)[:, :full], A6.view(K // 128, -1, 3072)[:, :full]), \
+        "fp6 form changes when the 4-bit codes are left out"
     # properties on all rows
     rs = meta[:, 2].to(torch.int64)
     assert torch.equal(rs, (Aq & 0x0F).to(torch.int64).sum(dim=1) + (Aq >> 4).to(torch.int64).sum(dim=1))
