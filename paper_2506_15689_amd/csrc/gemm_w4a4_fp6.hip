@@ -183,18 +183,20 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
             const v2i t = *reinterpret_cast<const v2i*>(tail_ptr);
             dst[0] = m[0]; dst[1] = m[1]; dst[2] = m[2]; dst[3] = m[3]; dst[4] = t[0]; dst[5] = t[1];
         };
+        // fragment number t of the read order B0, A0, B1, .., B(TN-1), A1, .., A(TM-1): the order in which the MFMAs
+        // (row block outer, column block inner) first need them
+        auto read_nth = [&](int t, const uint8_t* st, int kb, int set) {
+            if (t == 0) read_one(pb[set][0], st + b_row + moff[kb], st + tb[kb][0]);
+            else if (t == 1) read_one(pa[set][0], st + a_row + moff[kb], st + ta[kb][0]);
+            else if (t < TN + 1) read_one(pb[set][t - 1], st + b_row + (t - 1) * BLOCK + moff[kb], st + tb[kb][t - 1]);
+            else read_one(pa[set][t - TN], st + a_row + (t - TN) * BLOCK + moff[kb], st + ta[kb][t - TN]);
+        };
         auto read_frags = [&](const uint8_t* st, int kb, int set) {
     #pragma unroll
-            for (int i = 0; i < TM; ++i) read_one(pa[set][i], st + a_row + i * BLOCK + moff[kb], st + ta[kb][i]);
-    #pragma unroll
-            for (int j = 0; j < TN; ++j) read_one(pb[set][j], st + b_row + j * BLOCK + moff[kb], st + tb[kb][j]);
-        };
-        auto compute = [&](int set) {
-    #pragma unroll
-            for (int i = 0; i < TM; ++i)
-    #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[set][i], pb[set][j], acc[i][j], 2, 2, 0, 0, 0, 0);
+            for (int t = 0; t < TM + TN; ++t) {
+                read_nth(t, st, kb, set);
+                __builtin_amdgcn_sched_barrier(0);        // keep the order of the main loop (its waits count reads)
+            }
         };
 
 
@@ -218,6 +220,20 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
         first = false;
         read_frags(lds, 0, 0);
 
+        // Half a K-step: the TM*TN MFMAs of one k-block, with the fragment reads of the NEXT k-block issued between
+        // them, one fragment (two LDS reads) in front of each of the first TM+TN MFMAs, in the order in which the
+        // next half will need them (B0, A0, B1 .. , A1 ..).  Issuing all reads first and all MFMAs after made every
+        // wave of the compute unit queue at the LDS at the same time while the matrix cores idled, and then run
+        // its MFMAs while the LDS idled; interleaved, the two pipes work at the same time.
+        auto half = [&](int use_set, const uint8_t* rd_stage, int rd_kb, int rd_set, bool do_reads) {
+    #pragma unroll
+            for (int t = 0; t < TM * TN; ++t) {
+                if (do_reads && t < TM + TN) read_nth(t, rd_stage, rd_kb, rd_set);
+                const int i = t / TN, j = t % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa[use_set][i], pb[use_set][j], acc[i][j], 2, 2, 0, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
         // One K-step.  The last one is peeled off the loop: with the "is there a next stage to read" test inside the
         // loop, two paths meet in front of the second block of MFMAs, one of them without the reads of the next
         // stage in flight, and the compiler then waits for every outstanding LDS read there -- including the ones
@@ -226,18 +242,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINOCC) void gemm_w4a4_fp6_
             const uint8_t* st = lds + (ks % STAGES) * STAGE_BYTES;
             // the stage refilled now was read during step ks-1; every wave has passed that step's barrier
             if (ks + STAGES - 1 < ksteps) issue_loads(ks + STAGES - 1);
-            // kb = 0: read kb = 1 of this stage ahead
-            read_frags(st, 1, 1);
             __builtin_amdgcn_sched_barrier(0);
-            compute(0);
-            __builtin_amdgcn_sched_barrier(0);
-            // kb = 1: every read of this stage has been issued; pass the barrier (next stage complete and
-            // visible: all but the newest STAGES-2 loads have landed), then read the next stage's kb = 0
+            // kb = 0, reading kb = 1 of this stage ahead
+            half(0, st, 1, 1, true);
+            // every read of this stage has been issued; pass the barrier (next stage complete and visible: all but
+            // the newest STAGES-2 loads have landed), then kb = 1, reading the next stage's kb = 0 ahead
             if (STAGES >= 3 && ks + STAGES - 1 < ksteps) wait_loads_and_barrier<MIN_LOADS*(STAGES - 2)>(); else wait_loads_and_barrier<0>();
-            if (decltype(has_next)::value) read_frags(lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            compute(1);
-            __builtin_amdgcn_sched_barrier(0);
+            half(1, lds + ((ks + 1) % STAGES) * STAGE_BYTES, 0, 0, decltype(has_next)::value);
         };
         int ks = 0;
         for (; ks + 1 < ksteps; ++ks) k_step(ks, std::true_type{});
