@@ -179,19 +179,33 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
         const v2i t = *reinterpret_cast<const v2i*>(tail_ptr);
         dst[0] = m[0]; dst[1] = m[1]; dst[2] = m[2]; dst[3] = m[3]; dst[4] = t[0]; dst[5] = t[1];
     };
+    // fragment number t of the read order B0, A0, B1, A1: the order in which the MFMAs (token block outer, channel
+    // block inner) first need them
+    auto read_nth = [&](int t, const uint8_t* st, int kb, int set) {
+        if (t == 0) read_one(pb[set][0], st + b_row + moff[kb], st + tb[kb][0]);
+        else if (t == 1) read_one(pa[set][0], st + a_row + moff[kb], st + ta[kb][0]);
+        else if (t == 2) read_one(pb[set][1], st + b_row + G6G_BLOCK + moff[kb], st + tb[kb][1]);
+        else read_one(pa[set][1], st + a_row + G6G_BLOCK + moff[kb], st + ta[kb][1]);
+    };
     auto read_frags = [&](const uint8_t* st, int kb, int set) {
 #pragma unroll
-        for (int i = 0; i < G6G_TM; ++i) read_one(pa[set][i], st + a_row + i * G6G_BLOCK + moff[kb], st + ta[kb][i]);
-#pragma unroll
-        for (int j = 0; j < G6G_TN; ++j) read_one(pb[set][j], st + b_row + j * G6G_BLOCK + moff[kb], st + tb[kb][j]);
+        for (int t = 0; t < 4; ++t) {
+            read_nth(t, st, kb, set);
+            __builtin_amdgcn_sched_barrier(0);            // keep the order of the main loop (its waits count reads)
+        }
     };
     const v16f zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    auto compute = [&](int set, bool from_zero) {
+    // Half a group: the four MFMAs of one k-block with the fragment reads of the next k-block issued between them
+    // (all reads first and all MFMAs after makes every wave of the compute unit queue at the LDS together while
+    // the matrix cores idle, as in the per-token fp6 kernel).
+    auto half = [&](int use_set, bool from_zero, const uint8_t* rd_stage, int rd_kb, int rd_set, bool do_reads) {
 #pragma unroll
-        for (int i = 0; i < G6G_TM; ++i)
-#pragma unroll
-            for (int j = 0; j < G6G_TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pb[set][j], pa[set][i], from_zero ? zero : acc[i][j], 2, 2, 0, 0, 0, 0);
+        for (int t = 0; t < 4; ++t) {
+            if (do_reads) read_nth(t, rd_stage, rd_kb, rd_set);
+            const int i = t >> 1, j = t & 1;
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pb[use_set][j], pa[use_set][i], from_zero ? zero : acc[i][j], 2, 2, 0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
     // The weights are the first MFMA operand: accumulator register r of lane l belongs to token l % 32 of the row
     // block and to output channel 8*(r/4) + 4*(l/32) + r%4 of the column block.  A lane then needs one token record
@@ -228,10 +242,8 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
         // the operand stage refilled now was read during step g-1; every wave has passed that step's barrier
         const bool ahead = g + 2 < ngroups;
         if (ahead) issue_operands(g + 2);
-        read_frags(st, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
-        compute(0, true);
-        __builtin_amdgcn_sched_barrier(0);
+        half(0, true, st, 1, 1, true);
         // every read of this stage has been issued; pass the barrier behind which the next stage and the next
         // group's constants are complete and visible: only the operand loads just issued may stay in flight
         int raw_cs = 0;
@@ -240,7 +252,6 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
             // the constants slot refilled now was read at the end of step g-1, which every wave has left
             if (ahead) issue_constants(g + 2);
             if (swave < 2) raw_cs = convert_colsums_load(g + 1);
-            read_frags(lds + ((g + 1) % G6G_STAGES) * G6G_STAGE_BYTES, 0, 0);
         } else {
             // the last group's column sums were converted during the step before: make that visible
             g6g_wait_loads_and_barrier<0>();
@@ -260,8 +271,7 @@ __global__ __launch_bounds__(G6G_THREADS, 2) void gemm_w4a4_grouped_fp6_kernel(G
             for (int q = 0; q < 4; ++q)
                 csb[j][q] = *reinterpret_cast<const v4i*>(slot + 2048 + (wn * G6G_WN + j * 32 + 8 * q + 4 * rgrp) * 4);
         __builtin_amdgcn_sched_barrier(0);
-        compute(1, false);
-        __builtin_amdgcn_sched_barrier(0);
+        half(1, false, lds + ((g + 1) % G6G_STAGES) * G6G_STAGE_BYTES, 0, 0, decltype(has_next)::value);
         if (decltype(has_next)::value) {
             if (swave < 2) convert_colsums_store(g + 1, raw_cs);
         }

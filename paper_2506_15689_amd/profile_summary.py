@@ -29,7 +29,7 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 COPY_KIB = 262144.0
-LIB_KERNELS = ("gemm_w4a4", "gemv_w4a4", "rotate_quant", "linear_decode", "diag_read", "diag_stream", "pack_fp6")
+LIB_KERNELS = ("gemm_w4a4", "gemv_w4a4", "rotate_quant", "linear_decode", "diag_read", "diag_stream", "diag_mfma", "pack_fp6")
 SIMDS = 1024                     # 256 compute units x 4
 XCDS = 8
 
@@ -171,10 +171,12 @@ def main(argv=None):
         out.append("")
         out.append("```")
         for k in sorted(agg):
-            if not any(s in k for s in LIB_KERNELS) or "diag_" in k or "pack_fp6" in k:
+            if not any(s in k for s in LIB_KERNELS) or "diag_read" in k or "diag_stream" in k or "pack_fp6" in k:
                 continue
             c = {n: mean(v) for n, v in agg[k].items()}
             n = len(next(iter(agg[k].values())))
+            if n < 3:                                    # one-off preparation kernels
+                continue
             out.append(f"{k}   (launches {n}, mean duration under the counters {mean(span.get(k, [0])) / 1e3:.1f} us)")
             for name in names:
                 if name in c:
@@ -183,8 +185,13 @@ def main(argv=None):
             d = []
             if cyc > 0:
                 ns = mean(span.get(k, [0]))
-                if ns > 0:
+                if ns > 0 and cyc / ns <= 2.45:
                     d.append(f"shader clock {cyc / ns:.2f} GHz")
+                elif ns > 0:
+                    # a kernel of a few microseconds: the busy counter also covers the dispatch's ramp, so it does not
+                    # give the clock; percentages below are then against the nominal 2.4 GHz over the kernel's duration
+                    cyc = 2.4 * ns
+                    d.append("cycles taken as 2.4 GHz x duration (the GUI-active counter also covers the ramp of a kernel this short)")
                 if "SQ_VALU_MFMA_BUSY_CYCLES" in c:
                     d.append(f"MFMA pipe busy {100 * c['SQ_VALU_MFMA_BUSY_CYCLES'] / (SIMDS * cyc):.1f} % of SIMD cycles")
                 if "SQ_ACTIVE_INST_VALU" in c:
@@ -242,5 +249,39 @@ def main(argv=None):
         print("updated", path)
 
 
+def sweep_main(argv):
+    """profile_summary sweep --title T --out FILE --kernel NAME --bench-args-common "..." --point "label|bytes|DIR" ...:
+    one table of kernel-trace averages over several runs (token-count sweeps of the rotate+quant kernels)."""
+    p = argparse.ArgumentParser(prog="profile_summary sweep")
+    p.add_argument("--title", required=True)
+    p.add_argument("--out", required=True)
+    p.add_argument("--kernel", required=True, help="kernel name prefix to report")
+    p.add_argument("--bench-args-common", required=True)
+    p.add_argument("--point", action="append", default=[], help="'<bench args of the point>|<algorithmic bytes per launch>|<stats dir>'")
+    a = p.parse_args(argv)
+    out = [f"# rocprofv3 summary: {a.title}", "",
+           "One run per row (one MI355X, from the repository root after `cd /tmp && export TMPDIR=/tmp`; `$R` is the repository):", "",
+           f"    rocprofv3 --kernel-trace --stats --output-format csv -d out_<row> -- python3 $R/bench.py {a.bench_args_common} <row's arguments>",
+           "", "Algorithmic bytes = tokens * (2 K bf16 in + K/2 of codes + 16 of record), i.e. without the fp6 copy of the codes that",
+           "this design may write on top; GB/s and the fraction of the 8 TB/s HBM peak are priced on those bytes.", "", "```",
+           f"{'arguments':44s} {'kernel':58s} {'calls':>5s} {'avg_us':>9s} {'min_us':>9s} {'alg. MB':>9s} {'GB/s':>8s} {'of 8 TB/s':>9s}"]
+    for pt in a.point:
+        args_pt, nbytes, d = pt.split("|")
+        nbytes = float(nbytes)
+        rows = [r for r in read_stats(d) if r[0].startswith(a.kernel)]
+        for k, calls, avg, mn, mx, pct in rows:
+            if calls < 3:
+                continue
+            gbs = nbytes / (avg * 1e-6) / 1e9
+            out.append(f"{args_pt:44s} {k[:58]:58s} {calls:5d} {avg:9.2f} {mn:9.2f} {nbytes / 1e6:9.2f} {gbs:8.0f} {gbs / 8000.0:9.3f}")
+    out.append("```")
+    with open(a.out, "w") as f:
+        f.write("\n".join(out) + "\n")
+    print("wrote", a.out)
+
+
 if __name__ == "__main__":
-    main()
+    if len(sys.argv) > 1 and sys.argv[1] == "sweep":
+        sweep_main(sys.argv[2:])
+    else:
+        main()
