@@ -365,3 +365,71 @@ def test_prepare_weights_against_the_oracle(N, K, with_bias, with_layer_bias):
         got = W6.cpu().numpy().reshape(K // 128, -1, 3072)
         want = layout_ref.pack_fp6(wq.codes).reshape(K // 128, -1, 3072)
         np.testing.assert_array_equal(got[:, :full // 32], want[:, :full // 32], err_msg="prepacked weights")
+
+
+def test_operands_between_two_and_four_gib():
+    """The matrix-path kernels address their packed operands with 32-bit unsigned byte offsets, so an operand may be
+    up to 4 GiB.  524288 + 45 tokens of K = 8192 (four times the largest batch of Sec. 5.2's prefill table, 131072
+    tokens) make the 4-bit activations 2.0 GiB and their fp6 form 3.0 GiB: the rows behind byte 2^31 of either form
+    must come out as the oracle computes them -- codes and records bit-exact, accumulators bit-exact on both matrix
+    paths, outputs within one bf16 step on identical codes -- and the two paths must agree on every element."""
+    K, N = 8192, 192
+    M = 524288 + 45
+    announce(f"operands between 2 and 4 GiB: M={M} K={K} N={N}")
+    gen = torch.Generator(device=DEV).manual_seed(2031)
+    X = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    for i in range(0, M, 65536):
+        n = min(65536, M - i)
+        X[i:i + n] = (torch.randn((n, K), generator=gen, device=DEV) * 1.5).to(torch.bfloat16)
+    X[:, 7] *= 20.0
+    bias = torch.randn(K, generator=gen, device=DEV) * 0.3
+    W = (torch.randn((N, K), generator=gen, device=DEV) * 0.02).to(torch.bfloat16)
+    Wq, w_scale, w_zero, w_sum = B.alloc_weight_buffers(N, K, DEV)
+    B.basq_quantize_weights(W, Wq, w_scale, w_zero, w_sum)
+    out_bias = torch.empty(N, dtype=torch.float32, device=DEV)
+    B.basq_fused_bias(Wq, w_scale, w_zero, bias, None, out_bias)
+    W6 = B.alloc_fp6_buffer(N, K, DEV)
+    B.basq_pack_fp6(Wq, W6)
+
+    Aq, meta = B.alloc_activation_buffers(M, K, DEV)
+    A6 = B.alloc_fp6_buffer(M, K, DEV)
+    assert 2 ** 31 < Aq.numel() < 2 ** 32 and 2 ** 31 < A6.numel() < 2 ** 32
+    clip = 0.9
+    B.basq_rotate_quant(X, K, bias, None, clip, clip, Aq, meta, Aq6=A6)
+    torch.cuda.synchronize()
+    # rows around byte 2^31 of the 4-bit form (row 524288), the first and last rows, and a random sample; the fp6
+    # form is laid out chunk by chunk of 128 channels, so every row has codes on both sides of its byte 2^31
+    rng = np.random.default_rng(2031)
+    cross4 = 2 ** 31 // (K // 2)
+    chunk6 = 2 ** 31 // (3072 * ((M + 31) // 32))                 # the 128-channel chunk of the fp6 form that straddles 2^31
+    rows = set(range(8)) | set(range(cross4 - 40, min(M, cross4 + 45))) | set(range(M - 45, M))
+    rows |= set(int(v) for v in rng.choice(M, 64, replace=False))
+    rows = np.array(sorted(rows))
+    announce(f"  4-bit form crosses 2^31 at row {cross4}; fp6 form inside chunk {chunk6} of {K // 128} "
+             f"(every row has codes behind it); {len(rows)} rows sampled")
+    ref_q = pu.check_rows_against_oracle(X, rows, K, bias, None, clip, clip, Aq, meta, what="operands beyond 2 GiB")
+    check_fp6_copy(Aq, A6, K, row_blocks=[0, cross4 // 32 - 1, cross4 // 32, M // 32 - 1])
+
+    acc8 = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    Y8 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y8, acc8)
+    acc6 = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+    Y6 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.basq_w4a4_gemm(Aq, meta, Wq, w_scale, w_zero, w_sum, out_bias, Y6, acc6, Aq6=A6, Wq6=W6)
+    torch.cuda.synchronize()
+    assert torch.equal(acc6, acc8), "accumulators of the fp6 and int8 paths differ"
+    assert torch.equal(Y6.view(torch.int16), Y8.view(torch.int16)), "outputs of the fp6 and int8 paths differ"
+    assert not torch.isnan(Y6).any()
+
+    wq_ref = oracle.quantize_weights(oracle.bf16_to_f32(si.bf16_bits(W.cpu())))
+    np.testing.assert_array_equal(oracle.unpack_codes(Wq.cpu().numpy()), wq_ref.codes)
+    c_ref = oracle.fused_bias(wq_ref, bias.cpu().numpy(), None)
+    t_rows = torch.from_numpy(rows).to(DEV)
+    acc_ref = oracle.int_gemm_blas(ref_q.codes, wq_ref.codes)
+    np.testing.assert_array_equal(acc6[t_rows].cpu().numpy(), acc_ref, err_msg="accumulators behind 2^31")
+    y_ref = oracle.dequant(acc_ref, ref_q, wq_ref, c_ref)
+    y = oracle.bf16_to_f32(si.bf16_bits(Y6[t_rows].cpu())).astype(np.float64)
+    top = float(np.abs(y_ref).max())
+    worst = float((np.abs(y - y_ref) - 2.0 ** -8 * np.abs(y_ref)).max() / top)
+    assert worst <= 1e-5, f"worst excess over one bf16 step: {worst} of max|ref| on identical codes"
+    announce(f"ok worst excess {worst:.2e}")
