@@ -367,15 +367,18 @@ def test_prepare_weights_against_the_oracle(N, K, with_bias, with_layer_bias):
         np.testing.assert_array_equal(got[:, :full // 32], want[:, :full // 32], err_msg="prepacked weights")
 
 
-def test_operands_between_two_and_four_gib():
+@pytest.mark.parametrize("M", [524288 + 45, 1048576 + 19])
+def test_packed_operands_of_two_to_four_gib_and_beyond(M):
     """The matrix-path kernels address their packed operands with 32-bit unsigned byte offsets, so an operand may be
     up to 4 GiB.  524288 + 45 tokens of K = 8192 (four times the largest batch of Sec. 5.2's prefill table, 131072
     tokens) make the 4-bit activations 2.0 GiB and their fp6 form 3.0 GiB: the rows behind byte 2^31 of either form
     must come out as the oracle computes them -- codes and records bit-exact, accumulators bit-exact on both matrix
-    paths, outputs within one bf16 step on identical codes -- and the two paths must agree on every element."""
+    paths, outputs within one bf16 step on identical codes -- and the two paths must agree on every element.
+    1048576 + 19 tokens put both forms beyond 4 GiB: the quantiser and the repacking kernel index with 64 bits, and
+    the product falls back to the kernel that does too (with or without the fp6 operands); same checks, around byte
+    2^32 as well."""
     K, N = 8192, 192
-    M = 524288 + 45
-    announce(f"operands between 2 and 4 GiB: M={M} K={K} N={N}")
+    announce(f"packed operands of {M * (K // 2) / 2 ** 30:.2f} GiB (4-bit) and {M * K * 0.75 / 2 ** 30:.2f} GiB (fp6): M={M} K={K} N={N}")
     gen = torch.Generator(device=DEV).manual_seed(2031)
     X = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
     for i in range(0, M, 65536):
@@ -393,7 +396,7 @@ def test_operands_between_two_and_four_gib():
 
     Aq, meta = B.alloc_activation_buffers(M, K, DEV)
     A6 = B.alloc_fp6_buffer(M, K, DEV)
-    assert 2 ** 31 < Aq.numel() < 2 ** 32 and 2 ** 31 < A6.numel() < 2 ** 32
+    assert Aq.numel() > 2 ** 31 and A6.numel() > 2 ** 31 and (Aq.numel() < 2 ** 32) == (M < 1048576)
     clip = 0.9
     B.basq_rotate_quant(X, K, bias, None, clip, clip, Aq, meta, Aq6=A6)
     torch.cuda.synchronize()
@@ -403,12 +406,15 @@ def test_operands_between_two_and_four_gib():
     cross4 = 2 ** 31 // (K // 2)
     chunk6 = 2 ** 31 // (3072 * ((M + 31) // 32))                 # the 128-channel chunk of the fp6 form that straddles 2^31
     rows = set(range(8)) | set(range(cross4 - 40, min(M, cross4 + 45))) | set(range(M - 45, M))
+    if M > 2 * cross4:
+        rows |= set(range(2 * cross4 - 40, min(M, 2 * cross4 + 45)))      # byte 2^32
     rows |= set(int(v) for v in rng.choice(M, 64, replace=False))
     rows = np.array(sorted(rows))
     announce(f"  4-bit form crosses 2^31 at row {cross4}; fp6 form inside chunk {chunk6} of {K // 128} "
              f"(every row has codes behind it); {len(rows)} rows sampled")
     ref_q = pu.check_rows_against_oracle(X, rows, K, bias, None, clip, clip, Aq, meta, what="operands beyond 2 GiB")
     check_fp6_copy(Aq, A6, K, row_blocks=[0, cross4 // 32 - 1, cross4 // 32, M // 32 - 1])
+    torch.cuda.empty_cache()
 
     acc8 = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
     Y8 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
