@@ -36,6 +36,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 / fp4 MFMA, published
+# 256 compute units x 4 SIMDs at 2.4 GHz, one 64-lane vector instruction per four cycles per SIMD (16 lanes wide;
+# the published 157.3 TFLOP/s fp32 figure counts packed two-element fused multiply-adds, which this build does not use)
+VALU_ISSUE_PEAK_G = 256 * 4 * 2.4 / 4
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 OTHER_WORKLOADS = ("C2", "C4", "C3_M1", "C3_M4", "C3_M16")
 
@@ -99,12 +102,13 @@ def load_traffic():
         return {}
 
 
-def traffic_of(table, workload, kernel):
-    """HBM-side bytes per launch of `kernel` (name prefix) on `workload` from the tracked counter summary, or None."""
+def traffic_of(table, workload, kernel, field="bytes_per_launch"):
+    """HBM-side bytes per launch of `kernel` (name prefix) on `workload` from the tracked counter summary (or another
+    field of its entry), or None."""
     for key, ent in table.get("entries", {}).items():
         w, _, k = key.partition("/")
         if w == workload and k.startswith(kernel):
-            return ent.get("bytes_per_launch")
+            return ent.get(field)
     return None
 
 
@@ -405,6 +409,14 @@ def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M
                "frac": rq_gbs / HBM_PEAK_GBS, "traffic": rq_traffic, "algorithmic_bytes": rq_bytes,
                "writes_4bit_codes": not fp6_only, "design_bytes": rq_design, "achieved_on_design_bytes": rq_design / (rq_ms * 1e-3) / 1e9,
                "traffic_over_algorithmic": (rq_traffic / rq_bytes) if rq_traffic else None, **spread(t_rq)}
+    # The same kernel against the vector pipes' issue rate, which is what bounds it (one wave instruction per four
+    # cycles per SIMD: packed fp32 is not used): vector instructions per launch from the tracked counter summary.
+    rq_valu = traffic_of(table, config, rq_kernel, "valu_insts_per_launch")
+    if rq_valu:
+        ach = rq_valu / (rq_ms * 1e-3) / 1e9
+        roof_rq["alu"] = {"bound": "alu", "achieved": ach, "peak": VALU_ISSUE_PEAK_G, "unit": "G wave-instructions/s",
+                          "frac": ach / VALU_ISSUE_PEAK_G, "valu_insts_per_launch": rq_valu,
+                          "valu_insts_per_token": rq_valu / max(M, 1)}
     if rq_only:
         roof = None
     elif decode:

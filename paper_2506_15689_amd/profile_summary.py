@@ -208,6 +208,12 @@ def main(argv=None):
                     d.append(f"... of which for LDS {100 * c['SQ_WAIT_INST_LDS'] / wc:.1f} %")
                 if "SQ_WAIT_ANY" in c:
                     d.append(f"waves waiting for anything {100 * c['SQ_WAIT_ANY'] / wc:.1f} % of wave cycles")
+            key = f"{a.workload}/{k}"
+            if key in entries:                           # instruction counts per launch, for the issue-rate view of bench.py
+                for nm, field in (("SQ_INSTS_VALU", "valu_insts_per_launch"), ("SQ_INSTS_MFMA", "mfma_insts_per_launch"),
+                                  ("SQ_WAVES", "waves_per_launch")):
+                    if nm in c:
+                        entries[key][field] = int(round(c[nm]))
             if c.get("SQ_WAVES"):
                 w = c["SQ_WAVES"]
                 for nm, label in (("SQ_INSTS_VALU", "VALU"), ("SQ_INSTS_MFMA", "MFMA"), ("SQ_INSTS_LDS", "LDS"), ("SQ_INSTS_VMEM", "VMEM")):
