@@ -8,7 +8,8 @@ that already sit in HBM.  Prints ONE JSON line:
   value        whole-layer throughput, 2*M*N*K integer operations per second of step time (TOPS)
   roofline     the dominant kernel (the GEMM, bound by the matrix cores; for decode shapes HBM bound)
   roofline_rotate_quant   the rotate+bias+quant kernel against HBM bandwidth, priced on the method's own bytes
-               (2.5 per channel + 16 per token); the bytes of the design's fp6 copy are reported beside it
+               (2.5 per channel + 16 per token); the bytes of the design's fp6 copy are reported beside it, and under
+               "alu" the same launch against the vector pipes' issue rate (instructions from the counter summaries)
   other_workloads   the remaining workloads of the definition (C2, C4 prefill; C3 decode with 1, 4, 16 tokens),
                measured in the same process after the headline one
   cpu_baseline the CPU oracle timed on a bounded sample of the same workload, on all host threads and on one
@@ -499,6 +500,9 @@ def compact(full):
                                                 "avg_kernel_ms", "min_kernel_ms", "median_kernel_ms") if q.get(k) is not None}}
     if "int8_path" in r:
         c["dominant"]["int8_path_frac_of_int8_peak"] = r["int8_path"]["frac"]
+    if "alu" in q:
+        c["rotate_quant"]["valu_issue_frac"] = q["alu"]["frac"]
+        c["rotate_quant"]["valu_insts_per_token"] = q["alu"]["valu_insts_per_token"]
     return c
 
 
