@@ -48,7 +48,41 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     const int M = (int)g.M;
     const int n0 = blockIdx.x * LD_ROWS;
 
-    // ---- phase 0: the weight stream ---------------------------------------------------------------
+    // ---- phase 0: requests, in the order their data is needed ----------------------------------------------
+    // Vector-memory loads of a wave complete in issue order, so whatever is requested behind the weight stream
+    // cannot be used before all of the wave's weights have arrived (3.8 us into the kernel).  The token and the
+    // channel bias are therefore requested first: the rotation then runs while the weights stream in.
+    v8bf bop[2];
+    p2_make_bop<NC, FOLD_NORM>(lane, bop);
+    const P2Lane pl = p2_lane(lane);
+    const bool split_mode = M * NWAY <= LD_WAVES;                       // uniform over the grid
+    uint4 raw[NC];
+    uint4 raw4[4] = {};
+    auto load_token = [&](int t) {
+        const uint16_t* x = q.X + t * q.ldx + 8 * pl.chunk;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
+    };
+    if (split_mode) {
+        const int t = wave / NWAY, half = wave % NWAY;
+        if (t < M) {
+            const uint16_t* x = q.X + t * q.ldx + 8 * pl.chunk + 2048 * half;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
+        }
+    } else if (wave < M) {
+        load_token(wave);
+    }
+    // b^c: K / 4 / 256 = 4 or 8 float4 pieces per thread, held in named registers until they are staged below (an
+    // array here ends up in LDS scratch, whose store would wait for the data at once)
+    constexpr int BIAS_PIECES = HAS_BIAS ? K / 4 / LD_THREADS : 0;
+    static_assert(BIAS_PIECES <= 8, "eight pieces of the channel bias per thread at most");
+    float4 bp0 = {}, bp1 = {}, bp2 = {}, bp3 = {}, bp4 = {}, bp5 = {}, bp6 = {}, bp7 = {};
+#define LD_BIAS_LOAD(i) if (BIAS_PIECES > i) bp##i = *reinterpret_cast<const float4*>(q.bias + 4 * (tid + i * LD_THREADS))
+    LD_BIAS_LOAD(0); LD_BIAS_LOAD(1); LD_BIAS_LOAD(2); LD_BIAS_LOAD(3);
+    LD_BIAS_LOAD(4); LD_BIAS_LOAD(5); LD_BIAS_LOAD(6); LD_BIAS_LOAD(7);
+#undef LD_BIAS_LOAD
+    __builtin_amdgcn_sched_barrier(0);                   // keep the issue order: the compiler would move the weights up
     const uint8_t* wblk = g.Wq + (int64_t)n0 * KB + lane * 16;        // piece `lane` of each of the block's KBs
     v4i w[STEPS];
 #pragma unroll
@@ -57,37 +91,30 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     const int orow = tid & 15, otok = tid >> 4;
     const int on = n0 + orow;
     const bool out_ok = otok < M && on < g.N;
-    float sw = 0.f, zp = 0.f, ws = 0.f, cb = 0.f;
-    if (out_ok) {
-        sw = bf16_to_f32(g.w_scale[on]);
-        zp = bf16_to_f32(g.w_zero[on]);
-        ws = g.w_sum[on];
-        cb = g.out_bias ? g.out_bias[on] : 0.0f;
+    // the epilogue's constants: requested without a branch (clamped row) and converted only where they are used -- a
+    // conversion here would wait for them, and with them for the weights requested before them
+    const int on_c = on < g.N ? on : g.N - 1;
+    const uint16_t sw_bits = g.w_scale[on_c], zp_bits = g.w_zero[on_c];
+    const float ws = g.w_sum[on_c];
+    float cb = 0.0f;
+    if (g.out_bias) cb = g.out_bias[on_c];
+    __builtin_amdgcn_sched_barrier(0);
+    {                                                     // the staged layout of p2_stage_bias
+        float4* dst = reinterpret_cast<float4*>(lbias_s);
+#define LD_BIAS_STAGE(i) if (BIAS_PIECES > i) { const int e = 4 * (tid + i * LD_THREADS); \
+                                               dst[((e >> 11) * 8 + ((e & 31) >> 2)) * 64 + ((e & 2047) >> 5)] = bp##i; }
+        LD_BIAS_STAGE(0); LD_BIAS_STAGE(1); LD_BIAS_STAGE(2); LD_BIAS_STAGE(3);
+        LD_BIAS_STAGE(4); LD_BIAS_STAGE(5); LD_BIAS_STAGE(6); LD_BIAS_STAGE(7);
+#undef LD_BIAS_STAGE
     }
 
     // ---- phase 1: rotate + quantise the tokens into LDS ---------------------------------------------------
-    v8bf bop[2];
-    p2_make_bop<NC, FOLD_NORM>(lane, bop);
-    const P2Lane pl = p2_lane(lane);
-    uint4 raw[NC];
-    auto load_token = [&](int t) {
-        const uint16_t* x = q.X + t * q.ldx + 8 * pl.chunk;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) raw[c] = nt_load16(x + 512 * c);
-    };
     // Split mode: with so few tokens that every token can have NWAY waves, they share it (p2_token_split: same bits).
-    const bool split_mode = M * NWAY <= LD_WAVES;                       // uniform over the grid
     if (split_mode) {
         if (tid < LD_MAX_TOKENS) lsum_hi[tid] = 0;
         const int t = wave / NWAY, half = wave % NWAY;                  // token, and this wave's 2048-channel block of it
         const bool active = t < M;
-        uint4 raw4[4] = {};
-        if (active) {
-            const uint16_t* x = q.X + t * q.ldx + 8 * pl.chunk + 2048 * half;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
-        }
-        if (HAS_BIAS) p2_stage_bias<K>(lbias_s, q.bias, tid, LD_THREADS);   // complete behind the routine's first barrier
+        // (the staged bias is complete behind the routine's first barrier)
         const P2Meta tm = p2_token_split<NWAY, FOLD_NORM, HAS_BIAS, HAS_SCALE>(
             active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + t * (NWAY * 512), lred + t * (NWAY * 2),
             reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
@@ -106,11 +133,10 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
         }
     } else {
     if (tid < LD_MAX_TOKENS) lsum_hi[tid] = 0;
-    if (wave < M) load_token(wave);
-    if (HAS_BIAS) p2_stage_bias<K>(lbias_s, q.bias, tid, LD_THREADS);
-    __syncthreads();
-    for (int t = wave; t < M; t += LD_WAVES) {
-        if (t != wave) load_token(t);
+    p2_lds_barrier();                                    // the staged bias
+    static_assert(LD_MAX_TOKENS <= LD_WAVES, "one token per wave at most: it was requested in phase 0");
+    if (wave < M) {
+        const int t = wave;
         const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, false, false>(
             raw, bop, tr + wave * P2_LDS_WORDS, reinterpret_cast<const float4*>(lbias_s), q.act_scale, nullptr, norm,
             q.clip_lo, q.clip_hi, lane, pl.wbase, pl.rbase, []() {},
@@ -126,7 +152,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
         }
     }
     }
-    __syncthreads();
+    p2_lds_barrier();                                    // (not __syncthreads(): the weights may still be on their way)
 
     // ---- phase 2: product, reduction, de-quantisation ------------------------------------------------------
     const int row = lane & 15, sub = lane >> 4;          // operand lane: weight row / token `row`, k-block `sub`
@@ -147,12 +173,13 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     // accumulator register r of lane l: weight row 4*(l/16) + r, token l%16
 #pragma unroll
     for (int r = 0; r < 4; ++r) part[wave][(4 * sub + r) * 16 + row] = acc[r];
-    __syncthreads();
+    p2_lds_barrier();
     int av = 0;
 #pragma unroll
     for (int wv = 0; wv < LD_WAVES; ++wv) av += part[wv][orow * 16 + otok];
     if (out_ok) {
         const basq_tokmeta mt = lmeta[otok];
+        const float sw = bf16_to_f32(sw_bits), zp = bf16_to_f32(zp_bits);
         const float t = (float)av - zp * (float)(mt.rowsum + lsum_hi[otok]);
         const float y = fmaf(mt.scale * sw, t, fmaf(mt.lo, ws, cb));
         g.Y[(int64_t)otok * g.ldy + on] = f32_to_bf16(y);

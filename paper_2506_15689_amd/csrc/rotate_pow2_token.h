@@ -81,6 +81,13 @@ __device__ __forceinline__ int wave_sum_i(int v) {
 
 #define BFLY(x, y) do { const float _a = (x), _b = (y); (x) = _a + _b; (y) = _a - _b; } while (0)
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load the wave has
+// in flight, which here may be a caller's prefetch (the weight stream of the one-launch decode kernel) that nothing
+// on the other side of the barrier reads.
+__device__ __forceinline__ void p2_lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Per-lane constants of the routine.
 struct P2Lane {
     int chunk;      // global load: 16-byte chunk of the lane inside each 1 KB; bits (e3,e4,e5,e6,e7,e8) <- lane bits (2,3,0,1,4,5)
@@ -331,7 +338,7 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
 //   xch         NWAY * 512 float4 in LDS shared by the token's waves;  red: NWAY * 2 floats likewise
 //   sink(words, te, to) the 32 codes of channels 2048*part + 32*lane .. +31, packed two per byte, and the clamped
 //               values before rounding (even / odd channels) as in p2_token
-// Calls __syncthreads() twice: every wave of the workgroup calls it, `active` or not.  Returns the token's scale and
+// Meets the workgroup's other waves at two barriers (LDS traffic only): every wave calls it, `active` or not.  Returns the token's scale and
 // lower bound and the row sum of THIS wave's block; the caller adds the blocks.
 template <int NWAY, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
 __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const uint4 (&raw)[4], const v8bf (&bop)[2], float* wl,
@@ -376,7 +383,7 @@ __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const ui
             for (int h = 0; h < 2; ++h)
                 xch[(part * 8 + 2 * j + h) * 64 + lane] = make_float4(d[j][h][0], d[j][h][1], d[j][h][2], d[j][h][3]);
     }
-    __syncthreads();
+    p2_lds_barrier();
     float p[32];
     float mn = INFINITY, mx = -INFINITY;
     if (active) {
@@ -449,7 +456,7 @@ __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const ui
         mx = wave_max_f(mx);
         if (lane == 0) { red[2 * part] = mn; red[2 * part + 1] = mx; }
     }
-    __syncthreads();
+    p2_lds_barrier();
     P2Meta out;
     out.scale = 1.0f; out.lo = 0.0f; out.rowsum = 0;
     if (active) {
