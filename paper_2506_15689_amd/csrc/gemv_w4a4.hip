@@ -34,7 +34,7 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
     constexpr bool TWO_CHAINS = NT <= 2;            // few tiles: low and high nibbles on separate MFMA chains
     __shared__ int part[NT * 256];                  // cross-wave sums (integer adds: any order gives the same bits)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = blockIdx.x * (GV_ROWS * TILES);
     const int KB = a.K / 2;
     const int nchunks = KB / 64;               // 64-byte chunks per row (K % 128 == 0 checked by the caller)
@@ -65,20 +65,28 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
         arow[tt] = a.Aq + (int64_t)(t_ok[tt] ? 16 * tt + row : 0) * KB + sub * 16;
     }
 
-    // epilogue constants of the outputs this thread will finish (16 consecutive channels of one token per
-    // 16 threads, one such output per tile): requested now so that their latency overlaps the weight stream
+    // Epilogue constants and token records of the outputs this thread will finish (16 consecutive channels of one
+    // token per 16 threads, one such output per tile), requested now so that their latency overlaps the weight
+    // stream: without a branch (clamped indices) and as raw bits -- a conversion here would wait for them before
+    // the first weight load is issued, and a record fetched in the epilogue is a memory latency at the very end.
     const int orow = tid & 15, otok = tid >> 4;
-    float sw[TILES], zp[TILES], ws[TILES], cb[TILES];
+    uint16_t sw_bits[TILES], zp_bits[TILES];
+    float ws[TILES], cb[TILES];
 #pragma unroll
     for (int t = 0; t < TILES; ++t) {
         const int on = n0 + GV_ROWS * t + orow;
-        sw[t] = zp[t] = ws[t] = cb[t] = 0.f;
-        if (on < a.N) {
-            sw[t] = bf16_to_f32(a.w_scale[on]);
-            zp[t] = bf16_to_f32(a.w_zero[on]);
-            ws[t] = a.w_sum[on];
-            cb[t] = a.out_bias ? a.out_bias[on] : 0.0f;
-        }
+        const int on_c = on < a.N ? on : a.N - 1;
+        sw_bits[t] = a.w_scale[on_c];
+        zp_bits[t] = a.w_zero[on_c];
+        ws[t] = a.w_sum[on_c];
+        cb[t] = 0.0f;
+        if (a.out_bias) cb[t] = a.out_bias[on_c];
+    }
+    basq_tokmeta mts[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const int tok = 16 * tt + otok;
+        mts[tt] = a.meta[tok < M ? tok : M - 1];
     }
 
     v4i acc[NT], acc2[TWO_CHAINS ? NT : 1];
@@ -133,14 +141,15 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_w4a4_kernel(GemmArgs a) {
     for (int tt = 0; tt < TT; ++tt) {
         const int tok = 16 * tt + otok;
         if (tok >= M) continue;
-        const basq_tokmeta mt = a.meta[tok];
+        const basq_tokmeta mt = mts[tt];
 #pragma unroll
         for (int t = 0; t < TILES; ++t) {
             const int on = n0 + GV_ROWS * t + orow;
             if (on >= a.N) continue;
             const int av = part[(t * TT + tt) * 256 + orow * 16 + otok];
-            const float tv = (float)av - zp[t] * (float)mt.rowsum;
-            const float y = fmaf(mt.scale * sw[t], tv, fmaf(mt.lo, ws[t], cb[t]));
+            const float sw = bf16_to_f32(sw_bits[t]), zp = bf16_to_f32(zp_bits[t]);
+            const float tv = (float)av - zp * (float)mt.rowsum;
+            const float y = fmaf(mt.scale * sw, tv, fmaf(mt.lo, ws[t], cb[t]));
             a.Y[(int64_t)tok * a.ldy + on] = f32_to_bf16(y);
             if (a.acc_out) a.acc_out[(int64_t)tok * a.N + on] = av;
         }
