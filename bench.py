@@ -157,7 +157,7 @@ def cpu_baseline(config, sample_tokens, threads=None):
 
 # ---- one workload -----------------------------------------------------------------------------------------------
 
-def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M_override=0):
+def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M_override=0, also_graph=False):
     """Prepares `config` through the library, times `steps` steps of the whole path and each kernel on its own.
     Returns (fields of the JSON line for this workload, cfg, M)."""
     import torch
@@ -303,7 +303,7 @@ def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M
     t_step = timed(whole, steps)
     ms_step = t_step["mean"]
     graph_note = None
-    if args.graph:
+    if args.graph or also_graph:
         # the same K steps, recorded once on a capture stream and replayed: the device-side time of the step
         cap = torch.cuda.Stream()
         cap.wait_stream(stream)
@@ -322,8 +322,11 @@ def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M
         g.replay()
         e1.record(stream)
         torch.cuda.synchronize()
-        graph_note = {"eager_ms_per_step": ms_step}
-        ms_step = e0.elapsed_time(e1) / steps
+        if args.graph:
+            graph_note = {"eager_ms_per_step": ms_step}
+            ms_step = e0.elapsed_time(e1) / steps
+        else:                                             # reported beside the eager step, which stays the step
+            graph_note = {"graph_ms_per_step": e0.elapsed_time(e1) / steps}
     launches = max(steps, 50) if steps >= 10 else steps
     t_rq = timed(rotate_quant, launches)
     t_gemm = None if rq_only else timed(gemm, launches)
@@ -500,6 +503,8 @@ def compact(full):
                                                 "avg_kernel_ms", "min_kernel_ms", "median_kernel_ms") if q.get(k) is not None}}
     if "int8_path" in r:
         c["dominant"]["int8_path_frac_of_int8_peak"] = r["int8_path"]["frac"]
+    if full.get("graph", {}).get("graph_ms_per_step") is not None:
+        c["graph_ms_per_step"] = full["graph"]["graph_ms_per_step"]
     if "alu" in q:
         c["rotate_quant"]["valu_issue_frac"] = q["alu"]["frac"]
         c["rotate_quant"]["valu_insts_per_token"] = q["alu"]["valu_insts_per_token"]
@@ -548,8 +553,10 @@ def main():
     if plain and not args.no_other_workloads:
         others = {}
         for name in OTHER_WORKLOADS:
+            # decode-sized steps last a few microseconds, about what one call costs the host: their device-side time
+            # (the same steps replayed from a HIP graph) is reported beside the eager one
             full, _, _ = run_workload(args, name, max(10, min(args.steps, 50)), max(5, min(args.warmup, 10)),
-                                      with_ceilings=False, traffic_table=table)
+                                      with_ceilings=False, traffic_table=table, also_graph=name.startswith("C3"))
             others[name] = compact(full)
         out["other_workloads"] = others
 
