@@ -35,6 +35,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
                                                         // 16-byte pieces that fall on different bank groups
     __shared__ __attribute__((aligned(16))) float tr[LD_WAVES * P2_LDS_WORDS];
     __shared__ __attribute__((aligned(16))) float lbias_s[HAS_BIAS ? K : 4];
+    __shared__ __attribute__((aligned(16))) float lscale_s[HAS_SCALE ? K : 4];
     __shared__ __attribute__((aligned(16))) uint8_t xq[LD_MAX_TOKENS * XQ_STRIDE];
     __shared__ basq_tokmeta lmeta[LD_MAX_TOKENS];
     __shared__ int lsum_hi[LD_MAX_TOKENS];               // split mode: the row sums of a token's blocks other than the first
@@ -73,15 +74,19 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     } else if (wave < M) {
         load_token(wave);
     }
-    // b^c: K / 4 / 256 = 4 or 8 float4 pieces per thread, held in named registers until they are staged below (an
-    // array here ends up in LDS scratch, whose store would wait for the data at once)
-    constexpr int BIAS_PIECES = HAS_BIAS ? K / 4 / LD_THREADS : 0;
-    static_assert(BIAS_PIECES <= 8, "eight pieces of the channel bias per thread at most");
+    // b^c and s^a: K / 4 / 256 = 4 or 8 float4 pieces per thread each, held in named registers until they are staged
+    // below (an array here ends up in LDS scratch, whose store would wait for the data at once)
+    constexpr int VEC_PIECES = K / 4 / LD_THREADS;
+    constexpr int BIAS_PIECES = HAS_BIAS ? VEC_PIECES : 0, SCALE_PIECES = HAS_SCALE ? VEC_PIECES : 0;
+    static_assert(VEC_PIECES <= 8, "eight pieces of a channel vector per thread at most");
     float4 bp0 = {}, bp1 = {}, bp2 = {}, bp3 = {}, bp4 = {}, bp5 = {}, bp6 = {}, bp7 = {};
-#define LD_BIAS_LOAD(i) if (BIAS_PIECES > i) bp##i = *reinterpret_cast<const float4*>(q.bias + 4 * (tid + i * LD_THREADS))
-    LD_BIAS_LOAD(0); LD_BIAS_LOAD(1); LD_BIAS_LOAD(2); LD_BIAS_LOAD(3);
-    LD_BIAS_LOAD(4); LD_BIAS_LOAD(5); LD_BIAS_LOAD(6); LD_BIAS_LOAD(7);
-#undef LD_BIAS_LOAD
+    float4 sp0 = {}, sp1 = {}, sp2 = {}, sp3 = {}, sp4 = {}, sp5 = {}, sp6 = {}, sp7 = {};
+#define LD_VEC_LOAD(i) do { \
+        if (BIAS_PIECES > i) bp##i = *reinterpret_cast<const float4*>(q.bias + 4 * (tid + i * LD_THREADS)); \
+        if (SCALE_PIECES > i) sp##i = *reinterpret_cast<const float4*>(q.act_scale + 4 * (tid + i * LD_THREADS)); } while (0)
+    LD_VEC_LOAD(0); LD_VEC_LOAD(1); LD_VEC_LOAD(2); LD_VEC_LOAD(3);
+    LD_VEC_LOAD(4); LD_VEC_LOAD(5); LD_VEC_LOAD(6); LD_VEC_LOAD(7);
+#undef LD_VEC_LOAD
     __builtin_amdgcn_sched_barrier(0);                   // keep the issue order: the compiler would move the weights up
     const uint8_t* wblk = g.Wq + (int64_t)n0 * KB + lane * 16;        // piece `lane` of each of the block's KBs
     v4i w[STEPS];
@@ -100,12 +105,15 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     if (g.out_bias) cb = g.out_bias[on_c];
     __builtin_amdgcn_sched_barrier(0);
     {                                                     // the staged layout of p2_stage_bias
-        float4* dst = reinterpret_cast<float4*>(lbias_s);
-#define LD_BIAS_STAGE(i) if (BIAS_PIECES > i) { const int e = 4 * (tid + i * LD_THREADS); \
-                                               dst[((e >> 11) * 8 + ((e & 31) >> 2)) * 64 + ((e & 2047) >> 5)] = bp##i; }
-        LD_BIAS_STAGE(0); LD_BIAS_STAGE(1); LD_BIAS_STAGE(2); LD_BIAS_STAGE(3);
-        LD_BIAS_STAGE(4); LD_BIAS_STAGE(5); LD_BIAS_STAGE(6); LD_BIAS_STAGE(7);
-#undef LD_BIAS_STAGE
+        float4* dstb = reinterpret_cast<float4*>(lbias_s);
+        float4* dsts = reinterpret_cast<float4*>(lscale_s);
+#define LD_VEC_STAGE(i) do { \
+        const int e = 4 * (tid + i * LD_THREADS), at = ((e >> 11) * 8 + ((e & 31) >> 2)) * 64 + ((e & 2047) >> 5); \
+        if (BIAS_PIECES > i) dstb[at] = bp##i; \
+        if (SCALE_PIECES > i) dsts[at] = sp##i; } while (0)
+        LD_VEC_STAGE(0); LD_VEC_STAGE(1); LD_VEC_STAGE(2); LD_VEC_STAGE(3);
+        LD_VEC_STAGE(4); LD_VEC_STAGE(5); LD_VEC_STAGE(6); LD_VEC_STAGE(7);
+#undef LD_VEC_STAGE
     }
 
     // ---- phase 1: rotate + quantise the tokens into LDS ---------------------------------------------------
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
         // (the staged bias is complete behind the routine's first barrier)
         const P2Meta tm = p2_token_split<NWAY, FOLD_NORM, HAS_BIAS, HAS_SCALE>(
             active, half, raw4, bop, tr + wave * P2_LDS_WORDS, xch + t * (NWAY * 512), lred + t * (NWAY * 2),
-            reinterpret_cast<const float4*>(lbias_s), q.act_scale, norm, q.clip_lo, q.clip_hi, lane,
+            reinterpret_cast<const float4*>(lbias_s), reinterpret_cast<const float4*>(lscale_s), norm, q.clip_lo, q.clip_hi, lane,
             pl.wbase, pl.rbase, [&](const uint32_t (&words)[4], const v16f&, const v16f&) {
                 *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 1024 * half + 16 * lane) =
                     make_uint4(words[0], words[1], words[2], words[3]);
@@ -138,7 +146,8 @@ __global__ __launch_bounds__(LD_THREADS, 1) void linear_decode_kernel(RotateQuan
     if (wave < M) {
         const int t = wave;
         const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, false, false>(
-            raw, bop, tr + wave * P2_LDS_WORDS, reinterpret_cast<const float4*>(lbias_s), q.act_scale, nullptr, norm,
+            raw, bop, tr + wave * P2_LDS_WORDS, reinterpret_cast<const float4*>(lbias_s),
+            reinterpret_cast<const float4*>(lscale_s), nullptr, norm,
             q.clip_lo, q.clip_hi, lane, pl.wbase, pl.rbase, []() {},
             [&](int hf, int b, const uint32_t (&words)[4], const v16f&, const v16f&) {
                 *reinterpret_cast<uint4*>(xq + t * XQ_STRIDE + 2048 * hf + 1024 * b + 16 * lane) =

@@ -121,8 +121,9 @@ __device__ __forceinline__ void p2_make_bop(int lane, v8bf (&bop)[2]) {
     }
 }
 
-// The channel bias staged in LDS so that lane l's i-th 16-byte piece sits at float4 index (piece group)*64 + l:
-// conflict-free reads.  Called by all `nthreads` threads of the workgroup; the caller synchronises afterwards.
+// A per-channel vector (the channel bias b^c, the scale s^a) staged in LDS so that lane l's i-th 16-byte piece sits at
+// float4 index (piece group)*64 + l: conflict-free reads.  Called by all `nthreads` threads of the workgroup; the
+// caller synchronises afterwards.
 template <int K>
 __device__ __forceinline__ void p2_stage_bias(float* lds_bias, const float* bias, int tid, int nthreads) {
     float4* dst = reinterpret_cast<float4*>(lds_bias);
@@ -135,7 +136,9 @@ __device__ __forceinline__ void p2_stage_bias(float* lds_bias, const float* bias
 struct P2Meta { float scale, lo; int rowsum; };
 
 // raw: the token as loaded with P2Lane::chunk (raw[c] = 16 bytes at channel 512*c + 8*chunk).  wl: this wave's
-// P2_LDS_WORDS floats.  lbias: the staged bias.  rot_row: where the fp32 rotation of this token goes (ROT_OUT).
+// P2_LDS_WORDS floats.  lbias, lscale: b^c and s^a as staged by p2_stage_bias (s^a read from memory here would be
+// a load per 16 bytes behind whatever the caller has in flight -- its prefetched next token, a weight stream --
+// and loads complete in issue order).  rot_row: where the fp32 rotation of this token goes (ROT_OUT).
 // after_mfma(): called once raw[] is dead.  sink(hf, b, words, te, to): the 32 codes of channels
 // 4096*hf + 2048*b + 32*lane .. +31 -- words: packed two per byte (16 bytes); te[i] / to[i]: the clamped but not
 // yet rounded value fma(v, inv, nlo) in [0, 15] of channel 2i / 2i + 1, whose rounding to nearest-even is the code
@@ -148,7 +151,7 @@ struct P2Meta { float scale, lo; int rowsum; };
 template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED, class AfterMfma, class Sink,
           class GroupSink>
 __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2], float* wl, const float4* lbias,
-                                           const float* act_scale, float* rot_row, float norm, float clip_lo,
+                                           const float4* lscale, float* rot_row, float norm, float clip_lo,
                                            float clip_hi, int lane, int wbase, int rbase, AfterMfma&& after_mfma,
                                            Sink&& sink, GroupSink&& gsink) {
     constexpr int NH = NC / 8;                  // number of 4096-channel halves (bit 12)
@@ -245,7 +248,7 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
             for (int i4 = 0; i4 < 8; ++i4) {
                 float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
                 if (HAS_BIAS) bb = lbias[((2 * hf + b) * 8 + i4) * 64 + lane];
-                if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(act_scale + e0 + 4 * i4);
+                if (HAS_SCALE) ss = lscale[((2 * hf + b) * 8 + i4) * 64 + lane];
                 const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
                 const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
                 float rr[4];
@@ -342,7 +345,7 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
 // lower bound and the row sum of THIS wave's block; the caller adds the blocks.
 template <int NWAY, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, class Sink>
 __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const uint4 (&raw)[4], const v8bf (&bop)[2], float* wl,
-                                                 float4* xch, float* red, const float4* lbias, const float* act_scale,
+                                                 float4* xch, float* red, const float4* lbias, const float4* lscale,
                                                  float norm, float clip_lo, float clip_hi, int lane, int wbase, int rbase,
                                                  Sink&& sink) {
     static_assert(NWAY == 2 || NWAY == 4, "two waves for K = 4096, four for K = 8192");
@@ -439,7 +442,7 @@ __device__ __forceinline__ P2Meta p2_token_split(bool active, int part, const ui
         for (int i4 = 0; i4 < 8; ++i4) {
             float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
             if (HAS_BIAS) bb = lbias[(part * 8 + i4) * 64 + lane];
-            if (HAS_SCALE) ss = *reinterpret_cast<const float4*>(act_scale + e0 + 4 * i4);
+            if (HAS_SCALE) ss = lscale[(part * 8 + i4) * 64 + lane];
             const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
             const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
 #pragma unroll

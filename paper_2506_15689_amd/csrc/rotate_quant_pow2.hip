@@ -25,15 +25,20 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
     constexpr bool PREFETCH = (NC == 8);
     static_assert(WAVES == 4 || WAVES == 8, "workgroups of four or eight wavefronts");
     static_assert(!STAGE_TAILS || (WAVES == 8 && !GROUPED), "the staged tails are those of eight consecutive tokens");
-    // per-wave transpose buffers, then the channel bias (shared by the workgroup's waves), then the tail stage
+    // the channel bias and the channel scale (shared by the workgroup's waves; first, so that their reads are the
+    // array's base plus a constant an LDS instruction can carry: offsets up to 64 KB), then the per-wave transpose
+    // buffers, then the tail stage
     constexpr int BIAS_WORDS = HAS_BIAS ? K : 0;
+    constexpr int SCALE_WORDS = HAS_SCALE ? K : 0;
+    constexpr int VEC_WORDS = BIAS_WORDS + SCALE_WORDS;
     constexpr int TS_BYTES = STAGE_TAILS ? (K / 32) * WAVES * 8 : 0;      // per 32-channel group: 8 bytes per token
-    __shared__ __attribute__((aligned(16))) float lds[WAVES * P2_LDS_WORDS + BIAS_WORDS + TS_BYTES / 4];
-    uint8_t* const tstage = reinterpret_cast<uint8_t*>(lds + WAVES * P2_LDS_WORDS + BIAS_WORDS);
+    __shared__ __attribute__((aligned(16))) float lds[VEC_WORDS + WAVES * P2_LDS_WORDS + TS_BYTES / 4];
+    uint8_t* const tstage = reinterpret_cast<uint8_t*>(lds + VEC_WORDS + WAVES * P2_LDS_WORDS);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float* wl = lds + wave * P2_LDS_WORDS;
-    const float4* lbias = reinterpret_cast<const float4*>(lds + WAVES * P2_LDS_WORDS);
+    float* wl = lds + VEC_WORDS + wave * P2_LDS_WORDS;
+    const float4* lbias = reinterpret_cast<const float4*>(lds);
+    const float4* lscale = reinterpret_cast<const float4*>(lds + BIAS_WORDS);
     v8bf bop[2];
     p2_make_bop<NC, FOLD_NORM>(lane, bop);
     const P2Lane pl = p2_lane(lane);
@@ -59,10 +64,9 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
     // 64 registers live around the loop and the kernel spills)
     int64_t m = wave_id;
     if (PREFETCH && m < a.M) load_token(m);
-    if (HAS_BIAS) {
-        p2_stage_bias<K>(lds + WAVES * P2_LDS_WORDS, a.bias, threadIdx.x, THREADS);
-        __syncthreads();
-    }
+    if (HAS_BIAS) p2_stage_bias<K>(lds, a.bias, threadIdx.x, THREADS);
+    if (HAS_SCALE) p2_stage_bias<K>(lds + BIAS_WORDS, a.act_scale, threadIdx.x, THREADS);
+    if (HAS_BIAS || HAS_SCALE) __syncthreads();
 
     // One round per iteration: the workgroup's waves take WAVES consecutive tokens (a whole number of rounds for
     // every wave, since the staged variant meets at barriers).
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void r
         if (!PREFETCH) load_token(m);
         const int64_t mnext = m + wave_stride;
         const P2Meta tm = p2_token<NC, FOLD_NORM, HAS_BIAS, HAS_SCALE, ROT_OUT, GROUPED>(
-            raw, bop, wl, lbias, a.act_scale, ROT_OUT ? a.rot_out + m * (int64_t)K : nullptr, norm, a.clip_lo, a.clip_hi,
+            raw, bop, wl, lbias, lscale, ROT_OUT ? a.rot_out + m * (int64_t)K : nullptr, norm, a.clip_lo, a.clip_hi,
             lane, pl.wbase, pl.rbase,
             // prefetch the next token of this wave while the rest is computed (K = 4096: registers allow it)
             [&]() { if (PREFETCH && mnext < a.M) load_token(mnext); },
@@ -140,6 +144,7 @@ __global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuan
     constexpr int K = 512 * NC, NWAY = NC / 4, TOKENS = 4 / NWAY;
     __shared__ __attribute__((aligned(16))) float tr[4 * P2_LDS_WORDS];
     __shared__ __attribute__((aligned(16))) float lbias_s[HAS_BIAS ? K : 4];
+    __shared__ __attribute__((aligned(16))) float lscale_s[HAS_SCALE ? K : 4];
     __shared__ __attribute__((aligned(16))) float4 xch[4 * 512];
     __shared__ float lred[8];
     __shared__ int lsum[TOKENS];
@@ -158,9 +163,10 @@ __global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuan
         for (int j = 0; j < 4; ++j) raw4[j] = nt_load16(x + 512 * j);
     }
     if (HAS_BIAS) p2_stage_bias<K>(lbias_s, a.bias, tid, 256);          // complete behind the routine's first barrier
+    if (HAS_SCALE) p2_stage_bias<K>(lscale_s, a.act_scale, tid, 256);
     const P2Meta tm = p2_token_split<NWAY, NC == 8, HAS_BIAS, HAS_SCALE>(
         active, part, raw4, bop, tr + wave * P2_LDS_WORDS, xch + tl * (NWAY * 512), lred + tl * (NWAY * 2),
-        reinterpret_cast<const float4*>(lbias_s), a.act_scale, norm, a.clip_lo, a.clip_hi, lane,
+        reinterpret_cast<const float4*>(lbias_s), reinterpret_cast<const float4*>(lscale_s), norm, a.clip_lo, a.clip_hi, lane,
         pl.wbase, pl.rbase, [&](const uint32_t (&words)[4], const v16f& te, const v16f& to) {
             if (a.Aq) nt_store16(a.Aq + m * (int64_t)(K / 2) + 1024 * part + 16 * lane, make_uint4(words[0], words[1], words[2], words[3]));
             if (a.Aq6) {      // the fp6 copy, as in the one-wave kernel: group 64*part + lane of the token
@@ -191,7 +197,12 @@ __global__ __launch_bounds__(256) void rotate_quant_pow2_split_kernel(RotateQuan
 template <int NC, bool FOLD, bool HB, bool HS, bool RO, bool GR, int WAVES, bool STAGE>
 int launch_one(const RotateQuantArgs& a, hipStream_t s, float norm) {
     const int64_t want = (a.M + WAVES - 1) / WAVES;
-    const int64_t resident = 256 * (NC == 8 && WAVES == 4 ? 3 : 2) * 4 / WAVES;     // workgroups the chip holds at once
+    // workgroups the chip holds at once: by registers (the launch bounds) and by the 160 KB of LDS per compute unit
+    constexpr int K = 512 * NC;
+    constexpr int LDS_BYTES = 4 * (WAVES * P2_LDS_WORDS + (HB ? K : 0) + (HS ? K : 0)) + (STAGE ? (K / 32) * WAVES * 8 : 0);
+    constexpr int BY_REGS = (NC == 8 && WAVES == 4 ? 3 : 2) * 4 / WAVES, BY_LDS = 163840 / LDS_BYTES;
+    static_assert(BY_LDS >= 1, "the kernel's LDS must fit a compute unit");
+    const int64_t resident = 256 * (BY_REGS < BY_LDS ? BY_REGS : BY_LDS);
     const unsigned blocks = (unsigned)(want < resident ? want : resident);        // waves loop over tokens
     hipLaunchKernelGGL((rotate_quant_pow2_kernel<NC, FOLD, HB, HS, RO, GR, WAVES, STAGE>), dim3(blocks), dim3(WAVES * 64), 0, s, a, norm);
     return check_hip(hipGetLastError(), "rotate_quant (pow2) launch");
@@ -215,6 +226,9 @@ int launch_flags(const RotateQuantArgs& a, hipStream_t s, float norm) {
     // to 4096 for K = 8192 (4-10 %), and are neutral or slightly worse beyond.
     if (a.Aq6 && a.M >= 32768) return launch_one<NC, FOLD, HB, HS, false, false, 8, true>(a, s, norm);
     if (a.M >= 2048 && ((NC == 8 && a.M < 32768) || (NC == 16 && a.M <= 4096))) return launch_one<NC, FOLD, HB, HS, false, false, 8, false>(a, s, norm);
+    // K = 8192 with s^a staged next to b^c: a four-wave workgroup's 96 KB leave room for one per compute unit, one
+    // wave per SIMD; eight waves share the two vectors
+    if (NC == 16 && HS && a.M > 1024) return launch_one<NC, FOLD, HB, HS, false, false, 8, false>(a, s, norm);
     return launch_one<NC, FOLD, HB, HS, false, false, 4, false>(a, s, norm);
 }
 
