@@ -234,44 +234,36 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
 #pragma unroll
             for (int i = 0; i < 32; ++i) if ((i & 16) == 0) BFLY(p[hf][b][i], p[hf][b][i | 16]);
         }
-    // ---- normalise, bias, min/max ---------------------------------------------------------------
-    // this lane owns channels e = 4096*hf + 2048*b + 32*lane + i
+    // ---- normalise, bias, min/max; quantise, pack, store ------------------------------------------
+    // this lane owns channels e = 4096*hf + 2048*b + 32*lane + i.  Per-token ranges take two passes over the blocks
+    // (the range needs every value); with GROUPED a block is four lanes' own 128-channel group and is finished in
+    // one go, which keeps fewer values live.
     float mn = INFINITY, mx = -INFINITY;
-    float gmn[NH][2], gmx[NH][2];                   // GROUPED: the ranges of this lane's 32-channel runs
+    auto prepare_block = [&](int hf, int b) {         // v = s^a r - b^c in place; widens (mn, mx)
+        const int e0 = 4096 * hf + 2048 * b + 32 * lane;
 #pragma unroll
-    for (int hf = 0; hf < NH; ++hf)
+        for (int i4 = 0; i4 < 8; ++i4) {
+            float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (HAS_BIAS) bb = lbias[((2 * hf + b) * 8 + i4) * 64 + lane];
+            if (HAS_SCALE) ss = lscale[((2 * hf + b) * 8 + i4) * 64 + lane];
+            const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
+            const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
+            float rr[4];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            if (GROUPED) { mn = INFINITY; mx = -INFINITY; }
-            const int e0 = 4096 * hf + 2048 * b + 32 * lane;
-#pragma unroll
-            for (int i4 = 0; i4 < 8; ++i4) {
-                float4 bb = make_float4(0.f, 0.f, 0.f, 0.f), ss = make_float4(1.f, 1.f, 1.f, 1.f);
-                if (HAS_BIAS) bb = lbias[((2 * hf + b) * 8 + i4) * 64 + lane];
-                if (HAS_SCALE) ss = lscale[((2 * hf + b) * 8 + i4) * 64 + lane];
-                const float bv[4] = {bb.x, bb.y, bb.z, bb.w};
-                const float sv[4] = {ss.x, ss.y, ss.z, ss.w};
-                float rr[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float r = p[hf][b][4 * i4 + j];
-                    if (!FOLD_NORM) r = r * norm;
-                    rr[j] = r;
-                    const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
-                    p[hf][b][4 * i4 + j] = v;
-                    mn = fminf(mn, v);
-                    mx = fmaxf(mx, v);
-                }
-                if (ROT_OUT)
-                    *reinterpret_cast<float4*>(rot_row + e0 + 4 * i4) =
-                        make_float4(rr[0], rr[1], rr[2], rr[3]);
+            for (int j = 0; j < 4; ++j) {
+                float r = p[hf][b][4 * i4 + j];
+                if (!FOLD_NORM) r = r * norm;
+                rr[j] = r;
+                const float v = HAS_SCALE ? fmaf(r, sv[j], -bv[j]) : r - bv[j];
+                p[hf][b][4 * i4 + j] = v;
+                mn = fminf(mn, v);
+                mx = fmaxf(mx, v);
             }
-            gmn[hf][b] = mn; gmx[hf][b] = mx;
+            if (ROT_OUT)
+                *reinterpret_cast<float4*>(rot_row + e0 + 4 * i4) =
+                    make_float4(rr[0], rr[1], rr[2], rr[3]);
         }
-    if (!GROUPED) {
-        mn = wave_min_f(mn);
-        mx = wave_max_f(mx);
-    }
+    };
 
     // per-token constants, or (GROUPED) those of group (hf, b, lane/4)
     float lo, s, inv, nlo;
@@ -283,46 +275,55 @@ __device__ __forceinline__ P2Meta p2_token(uint4 (&raw)[NC], const v8bf (&bop)[2
         inv = __fdiv_rn(1.0f, s);
         nlo = -(lo * inv);
     };
-    if (!GROUPED) range_constants(mn, mx);
-
-    // ---- quantise, pack, store -----------------------------------------------------------------
     int sum = 0;
+    auto quantise_block = [&](int hf, int b) {          // codes of the block with the current constants; adds to sum
+        uint32_t words[4];
+        v16f te, to;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            uint32_t ev = 0, od = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j], inv, nlo), 0.0f, 15.0f);
+                const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
+                ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
+                od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
+                te[4 * w + j] = t0;
+                to[4 * w + j] = t1;
+            }
+            sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
+            sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
+            words[w] = ev | (od << 4);
+        }
+        sink(hf, b, words, te, to);
+    };
+
 #pragma unroll
     for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
+            if (GROUPED) { mn = INFINITY; mx = -INFINITY; }
+            prepare_block(hf, b);
             if (GROUPED) {
-                float vmin = gmn[hf][b], vmax = gmx[hf][b];
-                vmin = fminf(vmin, dpp_f<DPP_QUAD_XOR1>(vmin)); vmin = fminf(vmin, dpp_f<DPP_QUAD_XOR2>(vmin));
-                vmax = fmaxf(vmax, dpp_f<DPP_QUAD_XOR1>(vmax)); vmax = fmaxf(vmax, dpp_f<DPP_QUAD_XOR2>(vmax));
-                range_constants(vmin, vmax);
+                mn = fminf(mn, dpp_f<DPP_QUAD_XOR1>(mn)); mn = fminf(mn, dpp_f<DPP_QUAD_XOR2>(mn));
+                mx = fmaxf(mx, dpp_f<DPP_QUAD_XOR1>(mx)); mx = fmaxf(mx, dpp_f<DPP_QUAD_XOR2>(mx));
+                range_constants(mn, mx);
                 sum = 0;
-            }
-            uint32_t words[4];
-            v16f te, to;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                uint32_t ev = 0, od = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float t0 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j], inv, nlo), 0.0f, 15.0f);
-                    const float t1 = __builtin_amdgcn_fmed3f(fmaf(p[hf][b][8 * w + 2 * j + 1], inv, nlo), 0.0f, 15.0f);
-                    ev = __builtin_amdgcn_cvt_pk_u8_f32(t0, j, ev);     // round-half-to-even, NaN -> 0
-                    od = __builtin_amdgcn_cvt_pk_u8_f32(t1, j, od);
-                    te[4 * w + j] = t0;
-                    to[4 * w + j] = t1;
-                }
-                sum = __builtin_amdgcn_udot4(ev, 0x01010101u, sum, false);
-                sum = __builtin_amdgcn_udot4(od, 0x01010101u, sum, false);
-                words[w] = ev | (od << 4);
-            }
-            sink(hf, b, words, te, to);
-            if (GROUPED) {
+                quantise_block(hf, b);
                 sum += dpp_i<DPP_QUAD_XOR1>(sum);
                 sum += dpp_i<DPP_QUAD_XOR2>(sum);
                 gsink(hf, b, s, lo, sum);
             }
         }
+    if (!GROUPED) {
+        mn = wave_min_f(mn);
+        mx = wave_max_f(mx);
+        range_constants(mn, mx);
+#pragma unroll
+        for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) quantise_block(hf, b);
+    }
     if (!GROUPED) sum = wave_sum_i(sum);
     P2Meta out;
     out.scale = s; out.lo = lo; out.rowsum = sum;

@@ -7,6 +7,13 @@ namespace basq {
 
 namespace {
 
+// Waves per SIMD the kernel is compiled for: three (168 registers) for the plain K = 4096 four-wave variant, two (256)
+// for everything else -- K = 8192, and the variants that keep more per lane (group ranges, the fp32 rotation output)
+// and would spill at 168.
+constexpr int p2_waves_per_simd(int nc, int waves, bool rot_out, bool grouped) {
+    return (nc == 8 && waves == 4 && !rot_out && !grouped) ? 3 : 2;
+}
+
 // NC: 16-byte loads per lane per token (K = 512 * NC).  FOLD_NORM: 1/sqrt(K) is a power of two and
 // sits in the MFMA matrix; otherwise one fp32 multiply by `norm` follows the butterflies.
 // GROUPED: one range and one record per 128 channels (group_size = 128) instead of per token.
@@ -19,7 +26,7 @@ namespace {
 // of 65; staged it is 161 (measured: 65536 tokens of K = 4096 in 170 us against 222 us).  The two barriers per
 // round cost more than that saves below about 32768 tokens.
 template <int NC, bool FOLD_NORM, bool HAS_BIAS, bool HAS_SCALE, bool ROT_OUT, bool GROUPED, int WAVES, bool STAGE_TAILS>
-__global__ __launch_bounds__(WAVES * 64, (NC == 8 && WAVES == 4 ? 3 : 2)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
+__global__ __launch_bounds__(WAVES * 64, p2_waves_per_simd(NC, WAVES, ROT_OUT, GROUPED)) void rotate_quant_pow2_kernel(RotateQuantArgs a, float norm) {
     constexpr int K = 512 * NC;
     constexpr int THREADS = WAVES * 64;
     constexpr bool PREFETCH = (NC == 8);
@@ -200,7 +207,7 @@ int launch_one(const RotateQuantArgs& a, hipStream_t s, float norm) {
     // workgroups the chip holds at once: by registers (the launch bounds) and by the 160 KB of LDS per compute unit
     constexpr int K = 512 * NC;
     constexpr int LDS_BYTES = 4 * (WAVES * P2_LDS_WORDS + (HB ? K : 0) + (HS ? K : 0)) + (STAGE ? (K / 32) * WAVES * 8 : 0);
-    constexpr int BY_REGS = (NC == 8 && WAVES == 4 ? 3 : 2) * 4 / WAVES, BY_LDS = 163840 / LDS_BYTES;
+    constexpr int BY_REGS = p2_waves_per_simd(NC, WAVES, RO, GR) * 4 / WAVES, BY_LDS = 163840 / LDS_BYTES;
     static_assert(BY_LDS >= 1, "the kernel's LDS must fit a compute unit");
     const int64_t resident = 256 * (BY_REGS < BY_LDS ? BY_REGS : BY_LDS);
     const unsigned blocks = (unsigned)(want < resident ? want : resident);        // waves loop over tokens
