@@ -85,11 +85,12 @@ def check_fp6_copy(Aq, A6, K, row_blocks):
 
 # K = 4096: several waves per token up to 512 tokens, one wave per token in four-wave workgroups up to 2047,
 # eight-wave workgroups up to 32767, and from 32768 tokens on with the fp6 copy the staged tails.
-# K = 8192: split up to 256, four waves to 2047, eight waves to 4096, four waves beyond, staged tails from 32768.
+# K = 8192: split up to 256, four waves to 2047, eight waves to 4096, four waves beyond, staged tails from 32768;
+# with s^a (staged in LDS beside b^c) eight waves from 1025 tokens on.
 # K = 14336: two waves per token; four-wave workgroups, eight when both b^c and s^a are staged; 1024 tokens per round.
 SWITCH_CASES = [
     (4096, 12), (4096, 512), (4096, 513), (4096, 2047), (4096, 2048), (4096, 2061), (4096, 32768 + 13),
-    (8192, 11), (8192, 256), (8192, 257), (8192, 2047), (8192, 2048), (8192, 4096), (8192, 4097), (8192, 12301), (8192, 32768 + 13),
+    (8192, 11), (8192, 256), (8192, 257), (8192, 1024), (8192, 1025), (8192, 2047), (8192, 2048), (8192, 4096), (8192, 4097), (8192, 12301), (8192, 32768 + 13),
     (14336, 11), (14336, 131), (14336, 1030), (14336, 2048 + 5),
 ]
 
