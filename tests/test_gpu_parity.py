@@ -69,6 +69,17 @@ def test_blockwise_rotation(K, rot):
     run_case(si.make_tiny(48, K, 64, seed=K + rot), rot_size=rot)
 
 
+@pytest.mark.parametrize("M,K,N,rot", [(300, 4096, 11008, 4096), (260, 11008, 4096, 256), (3, 11008, 4096, 256),
+                                       (40, 4096, 11008, 4096)])
+def test_layer_shapes_of_the_model_the_paper_times(M, K, N, rot):
+    """Sec. 5.2 measures the prefill of a 7B LLaMA-2: hidden size 4096, MLP width 11008.  gate/up (K = 4096,
+    N = 11008: 43 tiles of 256 columns) with the full-width rotation; down (K = 11008 = 43 * 256, which has no
+    power-of-two or 28 * 2^t Hadamard of its own size) with the rotation applied blockwise on 256 channels, on the
+    tiled path, on the weight-streaming path (40 tokens) and for a few decode tokens."""
+    run_case(si.make_tiny(M, K, N, seed=K // 64 + M, act="swiglu" if K == 11008 else "gauss"), rot_size=rot,
+             use_blas_gemm=True)
+
+
 @pytest.mark.parametrize("K", [28 * 64, 28 * 16, 2 * 28 * 32])
 def test_kronecker_rotation_with_h28(K):
     rot = K if K != 2 * 28 * 32 else 28 * 32
