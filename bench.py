@@ -407,7 +407,9 @@ def run_workload(args, config, steps, warmup, *, with_ceilings, traffic_table, M
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     rq_kernel = ("rotate_quant_k28_kernel" if (K == 14336 and rot_size == K and group in (0, K)) else
                  "rotate_quant_pow2" if (K in (4096, 8192) and rot_size == K and group in (0, K, 128)) else
-                 "rotate_quant_head_kernel" if (rot_size == 128 and group == 128 and K % 512 == 0) else "rotate_quant_generic_kernel")
+                 "rotate_quant_head_kernel" if (rot_size == 128 and group == 128 and K % 512 == 0) else
+                 "rotate_quant_block_kernel" if (rot_size in (128, 256, 512) and group in (0, K) and K % 256 == 0 and
+                                                 K % rot_size == 0 and K <= 16384) else "rotate_quant_generic_kernel")
     rq_traffic = traffic_of(table, config, rq_kernel)
     roof_rq = {"kernel": rq_kernel, "bound": "hbm", "achieved": rq_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                "frac": rq_gbs / HBM_PEAK_GBS, "traffic": rq_traffic, "algorithmic_bytes": rq_bytes,

@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libbasq.so")
 
-SOURCES = ["api.hip", "hadamard28.hip", "rotate_quant.hip", "rotate_quant_pow2.hip", "rotate_quant_k28.hip", "rotate_quant_head.hip", "gemm_w4a4.hip", "gemm_w4a4_direct.hip", "gemm_w4a4_fp6.hip", "gemm_w4a4_grouped.hip", "gemm_w4a4_grouped_fp6.hip", "fp6_pack.hip", "gemv_w4a4.hip", "linear_decode.hip", "weights.hip", "diag.hip"]
+SOURCES = ["api.hip", "hadamard28.hip", "rotate_quant.hip", "rotate_quant_pow2.hip", "rotate_quant_k28.hip", "rotate_quant_head.hip", "rotate_quant_block.hip", "gemm_w4a4.hip", "gemm_w4a4_direct.hip", "gemm_w4a4_fp6.hip", "gemm_w4a4_grouped.hip", "gemm_w4a4_grouped_fp6.hip", "fp6_pack.hip", "gemv_w4a4.hip", "linear_decode.hip", "weights.hip", "diag.hip"]
 
 # -ffp-contract=off: the quantiser's fp32 sequence is part of the interface; fused multiply-adds
 # appear only where the source says fmaf.  Packed fp32 instructions are switched off.

@@ -38,6 +38,9 @@ int launch_rotate_quant_pow2(const RotateQuantArgs& a, hipStream_t s);
 // wave-local kernel for per-head work: rot_size == group == 128, K % 512 == 0 (rotate_quant_head.hip)
 bool rotate_quant_head_applicable(const RotateQuantArgs& a);
 int launch_rotate_quant_head(const RotateQuantArgs& a, hipStream_t s);
+// blockwise rotations of 128, 256 or 512 channels with per-token ranges, K <= 16384 (rotate_quant_block.hip)
+bool rotate_quant_block_applicable(const RotateQuantArgs& a);
+int launch_rotate_quant_block(const RotateQuantArgs& a, hipStream_t s);
 // kernel for rot_size == K == 14336 = 28 * 512 (rotate_quant_k28.hip)
 bool rotate_quant_k28_applicable(const RotateQuantArgs& a);
 int launch_rotate_quant_k28(const RotateQuantArgs& a, hipStream_t s);

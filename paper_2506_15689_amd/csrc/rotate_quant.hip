@@ -242,7 +242,8 @@ int launch_rotate_quant(const RotateQuantArgs& a, hipStream_t s) {
     if (rotate_quant_pow2_applicable(a)) return launch_rotate_quant_pow2(a, s);
     if (rotate_quant_k28_applicable(a)) return launch_rotate_quant_k28(a, s);
     if (rotate_quant_head_applicable(a)) return launch_rotate_quant_head(a, s);
-    const int rc = launch_rotate_quant_generic(a, s);
+    // the blockwise kernel and the generic one write the 4-bit codes only; the fp6 copy is made from them
+    const int rc = rotate_quant_block_applicable(a) ? launch_rotate_quant_block(a, s) : launch_rotate_quant_generic(a, s);
     if (rc != BASQ_OK || !a.Aq6 || !a.Aq) return rc;
     return launch_pack_fp6(a.Aq, a.M, a.K, a.Aq6, s);
 }

@@ -172,6 +172,30 @@ def test_degenerate_tokens_with_groupwise_ranges(K, M, rot, group, with_bias):
     pu.check_rows_against_oracle(X, rows, rot, bias, sa, 0.9, 0.95, Aq, meta, group=group, what="group-wise")
 
 
+@pytest.mark.parametrize("K,M,rot", [(11008, 300, 256), (1280, 70, 128), (2048, 41, 512), (768, 33, 256), (16384, 25, 512)])
+@pytest.mark.parametrize("with_bias,with_scale", [(False, False), (True, False), (True, True)])
+def test_degenerate_tokens_on_the_blockwise_kernel(K, M, rot, with_bias, with_scale):
+    """Blockwise rotations of 128, 256 and 512 channels with per-token ranges (the register-resident blockwise
+    kernel; K = 11008 and 768 end in a half piece of 256 channels): the degenerate tokens at both ends of the batch,
+    and ordinary tokens with one dead rotation block (zero, NaN, inf confined to it)."""
+    announce(f"degenerate tokens, blockwise K={K} M={M} rot={rot} bias={with_bias} scale={with_scale}")
+    X, bias, sa = gpu_inputs(M, K, seed=K + M + rot, with_bias=with_bias, with_scale=with_scale)
+    specials = [0, M - N_SPECIAL]
+    for f in reversed(specials):
+        plant_degenerate_rows(X, f)
+    X[12, rot:2 * rot] = 0.0
+    X[13, rot + 5] = float("nan")
+    X[14, K - rot + 9] = float("inf")
+    rows = np.arange(M) if M <= 80 else np.union1d(rows_to_check(M, specials, np.random.default_rng(M), n_random=48), [12, 13, 14])
+    Aq, meta = B.alloc_activation_buffers(M, K, DEV)
+    Aq.fill_(0xEE); meta.fill_(-7)
+    A6 = B.alloc_fp6_buffer(M, K, DEV)
+    B.basq_rotate_quant(X, rot, bias, sa, 0.9, 0.95, Aq, meta, Aq6=A6)
+    torch.cuda.synchronize()
+    pu.check_rows_against_oracle(X, rows, rot, bias, sa, 0.9, 0.95, Aq, meta, what="blockwise")
+    check_fp6_copy(Aq, A6, K, row_blocks=[0, (M // 32) - 1])
+
+
 @pytest.mark.parametrize("K", [4096, 8192])
 @pytest.mark.parametrize("M", [1, 2, 4])
 @pytest.mark.parametrize("with_bias", [False, True])

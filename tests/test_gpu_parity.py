@@ -80,6 +80,21 @@ def test_layer_shapes_of_the_model_the_paper_times(M, K, N, rot):
              use_blas_gemm=True)
 
 
+@pytest.mark.parametrize("M,K,N,rot", [(70, 256, 40, 128), (70, 256, 40, 256), (131, 512, 72, 512), (90, 768, 40, 256),
+                                       (90, 768, 40, 128), (150, 1280, 136, 256), (40, 2048, 64, 512), (33, 5632, 40, 512),
+                                       (140, 13824, 40, 512), (20, 16384, 24, 256), (20, 16384, 24, 128),
+                                       (20, 16640, 24, 256)])
+@pytest.mark.parametrize("scaled", [False, True])
+def test_blockwise_rotation_fast_kernel(M, K, N, rot, scaled):
+    """Blocks of 128, 256 or 512 channels with per-token ranges (the register-resident blockwise kernel): a token of
+    half a 512-channel piece, of one piece, of whole pieces plus a half, every piece count per wave up to the largest
+    K it takes (16384), and one size beyond it (the generic kernel); with and without s^a."""
+    lay = si.make_tiny(M, K, N, seed=K // 128 + rot + M, act="swiglu" if K % 1024 else "gauss")
+    sa = np.random.default_rng(K + rot).uniform(0.8, 1.25, K).astype(np.float32) if scaled else None
+    run_case(lay, rot_size=rot, use_blas_gemm=True, act_scale=sa, clip_lo=0.95 if scaled else None,
+             clip_hi=0.85 if scaled else None)
+
+
 @pytest.mark.parametrize("K", [28 * 64, 28 * 16, 2 * 28 * 32])
 def test_kronecker_rotation_with_h28(K):
     rot = K if K != 2 * 28 * 32 else 28 * 32
