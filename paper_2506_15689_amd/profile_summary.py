@@ -84,6 +84,7 @@ def main(argv=None):
     p.add_argument("--bench-json", help="file holding the JSON line bench.py printed in the --stats run")
     p.add_argument("--out", required=True)
     p.add_argument("--no-traffic-json", action="store_true")
+    p.add_argument("--commit", default="", help="commit the runs were made at (default: the current HEAD)")
     a = p.parse_args(argv)
 
     out = [f"# rocprofv3 summary: W4A4 rotated linear, {a.title}", ""]
@@ -239,10 +240,12 @@ def main(argv=None):
         table.setdefault("entries", {})
         for k in [k for k in table["entries"] if k.startswith(a.workload + "/")]:
             del table["entries"][k]
-        try:
-            commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], stdout=subprocess.PIPE, text=True).stdout.strip()
-        except OSError:
-            commit = ""
+        commit = a.commit
+        if not commit:
+            try:
+                commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], stdout=subprocess.PIPE, text=True).stdout.strip()
+            except OSError:
+                commit = ""
         for k, e in entries.items():
             e["measured_at_commit"] = commit
             e["summary"] = os.path.relpath(a.out, ROOT)
